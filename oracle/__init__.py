@@ -1,0 +1,192 @@
+"""ctypes front end of the CPU oracle (``zqfp_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, the smoke check and the
+benchmark's ``cpu_baseline`` leg.  Nothing here touches the HIP library and the
+HIP package never imports this module.  All arithmetic lives in the C file;
+this module only marshals numpy arrays.
+
+Array conventions (all C-contiguous numpy arrays):
+  X      uint16 [M, K]   bfloat16 bit patterns
+  W      uint16 [K, N]   bfloat16 bit patterns (input feature k, output channel n)
+  U, V   uint16 [K, r], [r, N]  binary16 bit patterns
+  Xq     uint8  [M, K]   E4M3 codes;  sx float32 [M]
+  codes  uint8  [K, N]   one E2M1 code per byte
+  exps   uint8  [K/G, N] exponent byte (n + 127 for a scale c[n] * 2^n)
+  c      float32 [N]     per-output-channel real scale (1 under M1)
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "zqfp_oracle.c")
+_LIB = os.path.join(_HERE, "libzqfp_oracle.so")
+
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+          "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+
+def build_oracle():
+    """Compile the oracle with gcc (always recompiles)."""
+    subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+            build_oracle()
+        L = ctypes.CDLL(_LIB)
+        c = ctypes
+        p = c.c_void_p
+        L.orc_e4m3_decode.restype = c.c_double
+        L.orc_e4m3_decode.argtypes = [c.c_uint8]
+        L.orc_e5m2_decode.restype = c.c_double
+        L.orc_e5m2_decode.argtypes = [c.c_uint8]
+        L.orc_e2m1_decode.restype = c.c_double
+        L.orc_e2m1_decode.argtypes = [c.c_uint8]
+        L.orc_e4m3_encode.restype = c.c_uint8
+        L.orc_e4m3_encode.argtypes = [c.c_float]
+        L.orc_e2m1_encode.restype = c.c_uint8
+        L.orc_e2m1_encode.argtypes = [c.c_double]
+        L.orc_fp4_to_fp8_shift.restype = c.c_int
+        L.orc_fp4_to_fp8_shift.argtypes = [c.c_uint8, c.c_int, c.c_int, c.POINTER(c.c_uint8)]
+        L.orc_quantize_act.restype = None
+        L.orc_quantize_act.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, p]
+        L.orc_pack_weight.restype = c.c_int64
+        L.orc_pack_weight.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, p, p, p]
+        L.orc_gemm.restype = None
+        L.orc_gemm.argtypes = [p, p, c.c_int64, c.c_int64, p, p, p, c.c_int64, c.c_int,
+                               p, p, c.c_int, p, p, c.c_int]
+        L.orc_gemm_samples.restype = None
+        L.orc_gemm_samples.argtypes = [p, p, c.c_int64, c.c_int64, p, p, p, c.c_int64, c.c_int,
+                                       p, p, c.c_int, p, p, c.c_int64, p, p]
+        L.orc_lorc_left.restype = None
+        L.orc_lorc_left.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int, p, p]
+        L.orc_max_threads.restype = c.c_int
+        L.orc_max_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _chk(a, dtype, ndim):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.ndim == ndim, (a.dtype, a.shape)
+    assert a.flags["C_CONTIGUOUS"]
+    return a
+
+
+# ---- scalar format functions -------------------------------------------------
+def e4m3_decode(code):
+    return lib().orc_e4m3_decode(int(code))
+
+
+def e5m2_decode(code):
+    return lib().orc_e5m2_decode(int(code))
+
+
+def e2m1_decode(code):
+    return lib().orc_e2m1_decode(int(code))
+
+
+def e4m3_encode(y):
+    return lib().orc_e4m3_encode(float(np.float32(y)))
+
+
+def e2m1_encode(y):
+    return lib().orc_e2m1_encode(float(y))
+
+
+def fp4_to_fp8_shift(code4, n, container):
+    """container: 'e4m3' or 'e5m2'.  Returns the FP8 code or None if the shifted
+    exponent is outside the container's normal range."""
+    out = ctypes.c_uint8(0)
+    rc = lib().orc_fp4_to_fp8_shift(int(code4), int(n), 1 if container == "e5m2" else 0,
+                                    ctypes.byref(out))
+    return None if rc else out.value
+
+
+# ---- array functions -----------------------------------------------------------
+def quantize_act(X):
+    _chk(X, np.uint16, 2)
+    M, K = X.shape
+    Xq = np.empty((M, K), np.uint8)
+    sx = np.empty((M,), np.float32)
+    lib().orc_quantize_act(_ptr(X), M, K, K, _ptr(Xq), _ptr(sx))
+    return Xq, sx
+
+
+def pack_weight(W, G, mode):
+    """mode 1 = M1, 2 = M2.  Returns codes, exps, c, number of saturated elements."""
+    _chk(W, np.uint16, 2)
+    K, N = W.shape
+    assert K % G == 0 and mode in (1, 2)
+    codes = np.empty((K, N), np.uint8)
+    exps = np.empty((K // G, N), np.uint8)
+    c = np.empty((N,), np.float32)
+    clipped = lib().orc_pack_weight(_ptr(W), K, N, N, G, mode, _ptr(codes), _ptr(exps), _ptr(c))
+    return codes, exps, c, int(clipped)
+
+
+def _lorc_args(T, V, M, N):
+    if T is None:
+        return None, None, 0
+    _chk(T, np.float32, 2)
+    _chk(V, np.uint16, 2)
+    r = T.shape[1]
+    assert T.shape[0] == M and V.shape == (r, N)
+    return T, V, r
+
+
+def gemm(Xq, sx, codes, exps, c, G, T=None, V=None, want_abs=True, threads=0):
+    """Y [M,N] float32 (and Sabs [M,N] float64, the sum of absolute terms)."""
+    _chk(Xq, np.uint8, 2), _chk(sx, np.float32, 1), _chk(codes, np.uint8, 2)
+    _chk(exps, np.uint8, 2), _chk(c, np.float32, 1)
+    M, K = Xq.shape
+    N = codes.shape[1]
+    assert codes.shape[0] == K and exps.shape == (K // G, N) and c.shape == (N,)
+    T, V, r = _lorc_args(T, V, M, N)
+    Y = np.empty((M, N), np.float32)
+    Sabs = np.empty((M, N), np.float64) if want_abs else None
+    lib().orc_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(codes), _ptr(exps), _ptr(c), N, G,
+                   _ptr(T), _ptr(V), r, _ptr(Y), _ptr(Sabs), int(threads))
+    return (Y, Sabs) if want_abs else Y
+
+
+def gemm_samples(Xq, sx, codes, exps, c, G, ms, ns, T=None, V=None):
+    _chk(Xq, np.uint8, 2), _chk(sx, np.float32, 1), _chk(codes, np.uint8, 2)
+    M, K = Xq.shape
+    N = codes.shape[1]
+    T, V, r = _lorc_args(T, V, M, N)
+    ms = np.ascontiguousarray(ms, np.int64)
+    ns = np.ascontiguousarray(ns, np.int64)
+    Y = np.empty(ms.shape, np.float32)
+    Sabs = np.empty(ms.shape, np.float64)
+    lib().orc_gemm_samples(_ptr(Xq), _ptr(sx), M, K, _ptr(codes), _ptr(exps), _ptr(c), N, G,
+                           _ptr(T), _ptr(V), r, _ptr(ms), _ptr(ns), ms.size, _ptr(Y), _ptr(Sabs))
+    return Y, Sabs
+
+
+def lorc_left(X, U):
+    """T = X.U (float32 [M,r]) and Tabs = sum |x.u| (float64 [M,r])."""
+    _chk(X, np.uint16, 2), _chk(U, np.uint16, 2)
+    M, K = X.shape
+    r = U.shape[1]
+    assert U.shape[0] == K
+    T = np.empty((M, r), np.float32)
+    Tabs = np.empty((M, r), np.float64)
+    lib().orc_lorc_left(_ptr(X), M, K, K, _ptr(U), r, _ptr(T), _ptr(Tabs))
+    return T, Tabs
+
+
+def max_threads():
+    return lib().orc_max_threads()
