@@ -1,0 +1,116 @@
+// C ABI of libzqfp (declared in include/zqfp.h): argument checks and kernel
+// dispatch.  No call here synchronizes, allocates or frees device memory.
+#include "../../include/zqfp.h"
+
+#include <string>
+
+#include "zqfp_internal.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int hip_fail(hipError_t e)
+{
+    g_last_error = hipGetErrorString(e);
+    return ZQFP_E_HIP;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
+                const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum, void* stream)
+{
+    if (M < 0 || N < 0 || r < 0 || r > 64) return ZQFP_E_SHAPE;
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L)) return ZQFP_E_SHAPE;
+    if (out_dtype != ZQFP_OUT_F32 && out_dtype != ZQFP_OUT_BF16) return ZQFP_E_MODE;
+    if (accum != ZQFP_ACCUM_EXACT && accum != ZQFP_ACCUM_FAST) return ZQFP_E_MODE;
+    if (M == 0 || N == 0) return ZQFP_OK;
+    if (!Xq || !sx || !packed || !Y) return ZQFP_E_NULL;
+    if (r > 0 && (!T || !V)) return ZQFP_E_NULL;
+    if (ldy < N) return ZQFP_E_SHAPE;
+    if (!aligned16(Xq) || !aligned16(Y) || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return ZQFP_E_ALIGN;
+    zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* blob = static_cast<const uint8_t*>(packed);
+    hipError_t e = zqfp::gemm_tile_supported(M, L)
+                       ? zqfp::launch_gemm_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                       : zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int zqfp_version(void) { return 100; }
+
+const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
+
+int zqfp_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U,
+                          int r, float* T, void* stream)
+{
+    if (M < 0 || K <= 0 || K % 128 != 0 || ldx < K || r < 0 || r > 64) return ZQFP_E_SHAPE;
+    if (M == 0) return ZQFP_OK;
+    if (!X || !Xq || !sx) return ZQFP_E_NULL;
+    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
+                                             static_cast<const uint16_t*>(U), r, T, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+size_t zqfp_packed_weight_bytes(int64_t K, int64_t N, int G)
+{
+    zqfp::BlobLayout L;
+    return zqfp::make_layout(K, N, G, &L) ? L.total : 0;
+}
+
+int zqfp_pack_weight_fp4(const void* W, int64_t K, int64_t N, int64_t ldw, int G, int mode, void* packed, void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L) || ldw < N) return ZQFP_E_SHAPE;
+    if (mode != ZQFP_SCALE_M1 && mode != ZQFP_SCALE_M2) return ZQFP_E_MODE;
+    if (!packed || (N > 0 && !W)) return ZQFP_E_NULL;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return ZQFP_E_ALIGN;
+    if (N == 0) return ZQFP_OK;
+    hipError_t e = zqfp::launch_pack_weight(static_cast<const uint16_t*>(W), ldw, L, mode, static_cast<uint8_t*>(packed),
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_unpack_codes(const void* packed, int64_t K, int64_t N, int G, uint8_t* codes, uint8_t* exps, float* colscale,
+                      void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L)) return ZQFP_E_SHAPE;
+    if (N == 0) return ZQFP_OK;
+    if (!packed || !codes || !exps || !colscale) return ZQFP_E_NULL;
+    hipError_t e = zqfp::launch_unpack(static_cast<const uint8_t*>(packed), L, codes, exps, colscale,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N)
+{
+    (void)M; (void)K; (void)N;
+    return 0;  // both GEMM forms reduce inside the workgroup
+}
+
+int zqfp_w4a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
+                   void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, void* stream)
+{
+    (void)workspace;
+    return gemm_common(Xq, sx, M, K, packed, N, G, nullptr, nullptr, 0, Y, ldy, out_dtype, accum, stream);
+}
+
+int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
+                        const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum,
+                        void* workspace, void* stream)
+{
+    (void)workspace;
+    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, stream);
+}
+
+}  // extern "C"

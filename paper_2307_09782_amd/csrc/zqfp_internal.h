@@ -1,0 +1,114 @@
+// Internal declarations shared by the HIP translation units of libzqfp.
+// Nothing here is part of the ABI (see include/zqfp.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace zqfp {
+
+// ---------------------------------------------------------------------------
+// Packed weight blob
+//
+//   [0, 256)            header (BlobHeader, little endian)
+//   codes               Np/16 strips x K/128 k-tiles x 1024 B "fragments".
+//                       A fragment is the B operand of one 16x16x128 (or half
+//                       of one 32x32x64 pair) block-scaled matrix instruction:
+//                       lane l (0..63) owns output channel n = 16*strip + l%16
+//                       and the 32 consecutive k = 128*ktile + 32*(l/16) + p,
+//                       p = 0..31, stored as 16 bytes, code p in byte p/2, even
+//                       p in the low nibble.  The fragment stores lane 0's 16
+//                       bytes first, so a wave reads it with one 16 B/lane load.
+//   exps                E8M0 exponent bytes, [Np/16][ngq][16 columns][4]: the
+//                       dword of (strip, quad q, column c) holds the bytes of
+//                       stored groups 4q..4q+3.  Stored groups have size Gs
+//                       (= G when G is a multiple of 128, else gcd(G,128)); a
+//                       real group larger than Gs repeats its byte.
+//   colscale            Np float32 (per-output-channel real scale; 1 under M1).
+//
+// Np = N rounded up to 16; padding columns hold zero codes, exponent byte 127
+// and colscale 0.
+// ---------------------------------------------------------------------------
+struct BlobHeader {
+    uint32_t magic;    // 'ZQF4'
+    uint32_t version;  // layout version
+    int64_t K, N, Np;
+    int32_t G, Gs, mode, ngs, ngq;
+    uint32_t pad_;
+    uint64_t off_codes, off_exps, off_colscale, total;
+};
+constexpr uint32_t kBlobMagic = 0x3446515Au;  // "ZQF4"
+constexpr uint32_t kBlobVersion = 1;
+
+struct BlobLayout {
+    int64_t K, N, Np, nstrips, nkt;
+    int G, Gs, ngs, ngq;
+    int gsb;        // 32-element blocks per stored group (Gs / 32)
+    int gsb_shift;  // log2(gsb) if gsb is a power of two, else -1
+    size_t off_codes, off_exps, off_colscale, total;
+};
+
+inline int gcd_int(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
+
+// Returns false if (K, N, G) violates the documented shape limits.
+inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
+{
+    if (K <= 0 || N < 0 || G <= 0 || K % 128 != 0 || G % 32 != 0 || K % G != 0) return false;
+    if (K / G > 256) return false;
+    L->K = K; L->N = N; L->Np = (N + 15) / 16 * 16;
+    L->nstrips = L->Np / 16; L->nkt = K / 128;
+    L->G = G; L->Gs = (G % 128 == 0) ? G : gcd_int(G, 128);
+    L->ngs = (int)(K / L->Gs); L->ngq = (L->ngs + 3) / 4;
+    L->gsb = L->Gs / 32;
+    L->gsb_shift = -1;
+    for (int s = 0; s < 16; ++s) if ((1 << s) == L->gsb) L->gsb_shift = s;
+    L->off_codes = 256;
+    L->off_exps = L->off_codes + (size_t)L->Np * (size_t)K / 2;
+    size_t exps_bytes = (size_t)L->nstrips * L->ngq * 64;
+    L->off_colscale = (L->off_exps + exps_bytes + 255) / 256 * 256;
+    L->total = (L->off_colscale + (size_t)L->Np * 4 + 255) / 256 * 256;
+    return true;
+}
+
+// IEEE binary16 bits -> binary32 (exact)
+__device__ inline float half_bits_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+// Splits the eight dwords of an E4M3 operand into the codes whose exponent field is >= 8
+// (bit 6 of the byte set) and the rest; the other bytes of each half are +0.  Inside either
+// half the exponents span at most 8 binades, which the matrix core's 8-wide dot unit sums
+// without dropping a bit.
+typedef int zq_v8i __attribute__((ext_vector_type(8)));
+__device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i& lo)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t x = (uint32_t)a[i];
+        const uint32_t m = ((x >> 6) & 0x01010101u) * 0xFFu;
+        hi[i] = (int)(x & m);
+        lo[i] = (int)(x & ~m);
+    }
+}
+
+// LoRC arguments of the GEMM epilogue (r == 0: none)
+struct Lorc {
+    const float* T;     // [M, r]
+    const uint16_t* V;  // [r, N] binary16 bits
+    int r;
+};
+
+// Launchers (each enqueues on `s` and returns the launch status).
+hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq,
+                               float* sx, const uint16_t* U, int r, float* T, hipStream_t s);
+hipError_t launch_pack_weight(const uint16_t* W, int64_t ldw, const BlobLayout& L, int mode,
+                              uint8_t* blob, hipStream_t s);
+hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* codes, uint8_t* exps,
+                         float* colscale, hipStream_t s);
+hipError_t launch_gemm_stream(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
+                              const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
+                              int accum, hipStream_t s);
+hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
+                            const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
+                            int accum, hipStream_t s);
+bool gemm_tile_supported(int64_t M, const BlobLayout& L);
+
+}  // namespace zqfp

@@ -1,0 +1,157 @@
+"""Thin Python binding of libzqfp (the C ABI in ``include/zqfp.h``).
+
+Argument marshalling only: every function takes torch tensors that live on
+the GPU, checks dtypes / contiguity, allocates the outputs with torch and
+passes raw device pointers plus the current HIP stream to the library.  No
+step of the path is computed here and there is no fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libzqfp.so")
+
+SCALE_M1, SCALE_M2 = 1, 2
+OUT_F32, OUT_BF16 = 0, 1
+ACCUM_EXACT, ACCUM_FAST = 0, 1
+
+_ERR = {-1: "ZQFP_E_NULL", -2: "ZQFP_E_SHAPE", -3: "ZQFP_E_ALIGN", -4: "ZQFP_E_MODE", -5: "ZQFP_E_HIP"}
+
+_lib = None
+
+
+class ZqfpError(RuntimeError):
+    def __init__(self, code, detail=""):
+        self.code = code
+        super().__init__(f"libzqfp: {_ERR.get(code, code)} {detail}".strip())
+
+
+def lib():
+    """Load libzqfp.so (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2307_09782_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        c, p, i64 = ctypes, ctypes.c_void_p, ctypes.c_int64
+        L.zqfp_version.restype = c.c_int
+        L.zqfp_last_hip_error.restype = c.c_char_p
+        L.zqfp_quantize_act_fp8.restype = c.c_int
+        L.zqfp_quantize_act_fp8.argtypes = [p, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_packed_weight_bytes.restype = c.c_size_t
+        L.zqfp_packed_weight_bytes.argtypes = [i64, i64, c.c_int]
+        L.zqfp_pack_weight_fp4.restype = c.c_int
+        L.zqfp_pack_weight_fp4.argtypes = [p, i64, i64, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_unpack_codes.restype = c.c_int
+        L.zqfp_unpack_codes.argtypes = [p, i64, i64, c.c_int, p, p, p, p]
+        L.zqfp_gemm_workspace_bytes.restype = c.c_size_t
+        L.zqfp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+        L.zqfp_w4a8_gemm.restype = c.c_int
+        L.zqfp_w4a8_gemm.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_w4a8_gemm_lorc.restype = c.c_int
+        L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p, p]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise ZqfpError(rc, lib().zqfp_last_hip_error().decode() if rc == -5 else "")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dev(t, dtype, ndim):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == ndim and t.is_contiguous()):
+        raise TypeError(f"expected a contiguous CUDA tensor of dtype {dtype} and {ndim} dims")
+    return t
+
+
+def quantize_act_fp8(X, U=None):
+    """X [M,K] bf16 (U [K,r] fp16) -> Xq [M,K] uint8 E4M3 codes, sx [M] f32 (, T [M,r] f32)."""
+    _dev(X, torch.bfloat16, 2)
+    M, K = X.shape
+    Xq = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    T, r = None, 0
+    if U is not None:
+        _dev(U, torch.float16, 2)
+        r = U.shape[1]
+        T = torch.empty((M, r), dtype=torch.float32, device=X.device)
+    _check(lib().zqfp_quantize_act_fp8(_ptr(X), M, K, X.stride(0), _ptr(Xq), _ptr(sx), _ptr(U), r, _ptr(T),
+                                       _stream(X)))
+    return (Xq, sx) if U is None else (Xq, sx, T)
+
+
+def packed_weight_bytes(K, N, G):
+    return int(lib().zqfp_packed_weight_bytes(K, N, G))
+
+
+def pack_weight_fp4(W, G, mode):
+    """W [K,N] bf16 -> opaque packed blob (uint8 tensor)."""
+    _dev(W, torch.bfloat16, 2)
+    K, N = W.shape
+    nbytes = packed_weight_bytes(K, N, G)
+    if nbytes == 0:
+        raise ZqfpError(-2, f"(K={K}, N={N}, G={G})")
+    packed = torch.empty((nbytes,), dtype=torch.uint8, device=W.device)
+    _check(lib().zqfp_pack_weight_fp4(_ptr(W), K, N, W.stride(0), G, mode, _ptr(packed), _stream(W)))
+    return packed
+
+
+def unpack_codes(packed, K, N, G):
+    """packed blob -> codes [K,N] uint8, exps [K/G,N] uint8, colscale [N] f32."""
+    _dev(packed, torch.uint8, 1)
+    codes = torch.empty((K, N), dtype=torch.uint8, device=packed.device)
+    exps = torch.empty((K // G, N), dtype=torch.uint8, device=packed.device)
+    colscale = torch.empty((N,), dtype=torch.float32, device=packed.device)
+    _check(lib().zqfp_unpack_codes(_ptr(packed), K, N, G, _ptr(codes), _ptr(exps), _ptr(colscale), _stream(packed)))
+    return codes, exps, colscale
+
+
+def gemm_workspace_bytes(M, K, N):
+    return int(lib().zqfp_gemm_workspace_bytes(M, K, N))
+
+
+def _workspace(M, K, N, device):
+    n = gemm_workspace_bytes(M, K, N)
+    return torch.empty((n,), dtype=torch.uint8, device=device) if n else None
+
+
+def w4a8_gemm(Xq, sx, packed, N, G, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
+    """Y [M,N] = (sx c) * (Xq . Wq)."""
+    _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
+    M, K = Xq.shape
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
+    ws = workspace if workspace is not None else _workspace(M, K, N, Xq.device)
+    _check(lib().zqfp_w4a8_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(Y), Y.stride(0), code, accum,
+                                _ptr(ws), _stream(Xq)))
+    return Y
+
+
+def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
+    """Y [M,N] = (sx c) * (Xq . Wq) + T . V."""
+    _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
+    _dev(T, torch.float32, 2), _dev(V, torch.float16, 2)
+    M, K = Xq.shape
+    r = T.shape[1]
+    if T.shape[0] != M or tuple(V.shape) != (r, N):
+        raise ZqfpError(-2, "LoRC factor shapes")
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
+    ws = workspace if workspace is not None else _workspace(M, K, N, Xq.device)
+    _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
+                                     Y.stride(0), code, accum, _ptr(ws), _stream(Xq)))
+    return Y

@@ -1,0 +1,277 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Quantized codes, token scales, exponent bytes and column
+scales must be bit-exact; GEMM outputs must meet the relative-Frobenius and
+the elementwise |err| <= 2^-18 * sum|a w| bounds."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2307_09782_amd import inputs, zqfp
+from _util import bf16_tensor, bits_equal_f32, check_gemm, f16_tensor, f32_tensor, u8_tensor
+
+pytestmark = pytest.mark.gpu
+
+CFG = inputs.CONFIGS
+
+
+def _sync_np(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------ quantizer
+@pytest.mark.parametrize("name,M", [("tiny", 16), ("opt1p3b_fc1", 300), ("llama7b_qkv", 1), ("llama7b_qkv", 77),
+                                    ("llama13b_ffn_lorc", 16), ("llama70b_ffn_decode", 64)])
+def test_quantizer_codes_and_scales_bit_exact(name, M):
+    cfg = CFG[name]
+    X = inputs.make_x(cfg, M)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(X))
+    assert np.array_equal(_sync_np(Xq), Xq_o)
+    assert bits_equal_f32(_sync_np(sx), sx_o)
+
+
+def test_quantizer_full_size_sampled_rows():
+    """Full-size launch (4096 x 4096); the oracle checks a sample of whole rows."""
+    cfg = CFG["llama7b_qkv"]
+    X = inputs.make_x(cfg, 4096)
+    Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(X))
+    rows = np.random.default_rng(0).choice(4096, 96, replace=False)
+    rows = np.concatenate([rows, [0, 4095]])
+    Xq_o, sx_o = oracle.quantize_act(np.ascontiguousarray(X[rows]))
+    assert np.array_equal(_sync_np(Xq)[rows], Xq_o)
+    assert bits_equal_f32(_sync_np(sx)[rows], sx_o)
+
+
+def test_quantizer_edge_rows_and_long_rows():
+    """Zero rows, signed zeros, vanishing rows, exact ties, a row longer than the
+    register-resident limit, and a strided input."""
+    rng = np.random.default_rng(2)
+    K = 128 * 80  # 10240 > 8192
+    x = rng.standard_normal((6, K)).astype(np.float32)
+    x[0] = 0.0
+    x[1] = 0.0; x[1, 5] = -0.0
+    x[2] = 2.0 ** -100; x[2, 9] = -(2.0 ** -100)
+    x[3, :] = np.resize(np.array([448, 42, -42, 1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -11, -0.0, 432], np.float32), K)
+    x[4, 17] = 3e38
+    X = inputs.f32_to_bf16_bits(x)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    big = torch.zeros((6, K + 64), dtype=torch.bfloat16, device="cuda")
+    big[:, :K] = bf16_tensor(X)
+    Xs = big[:, :K]  # row stride K + 64
+    Xq = torch.empty((6, K), dtype=torch.uint8, device="cuda")
+    sx = torch.empty((6,), dtype=torch.float32, device="cuda")
+    rc = zqfp.lib().zqfp_quantize_act_fp8(Xs.data_ptr(), 6, K, Xs.stride(0), Xq.data_ptr(), sx.data_ptr(), None, 0, None,
+                                          torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    assert np.array_equal(_sync_np(Xq), Xq_o)
+    assert bits_equal_f32(_sync_np(sx), sx_o)
+
+
+@pytest.mark.parametrize("name,M,r", [("tiny", 16, 8), ("llama13b_ffn_lorc", 16, 8), ("llama70b_ffn_decode", 4, 8),
+                                      ("tiny", 5, 3), ("tiny", 7, 16), ("tiny", 3, 40)])
+def test_lorc_left_factor(name, M, r):
+    cfg = CFG[name]
+    X = inputs.make_x(cfg, M)
+    U, _ = inputs.make_uv(cfg, rank=r)
+    T_o, Tabs = oracle.lorc_left(X, U)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    Xq, sx, T = zqfp.quantize_act_fp8(bf16_tensor(X), f16_tensor(U))
+    assert np.array_equal(_sync_np(Xq), Xq_o) and bits_equal_f32(_sync_np(sx), sx_o)
+    err = np.abs(_sync_np(T).astype(np.float64) - T_o)
+    assert (err / Tabs).max() <= 2.0 ** -18
+
+
+# ------------------------------------------------------------------ packer
+def _pack_and_compare(W, G, mode, cols=None):
+    K, N = W.shape
+    packed = zqfp.pack_weight_fp4(bf16_tensor(W), G, mode)
+    codes, exps, c = zqfp.unpack_codes(packed, K, N, G)
+    codes, exps, c = _sync_np(codes), _sync_np(exps), _sync_np(c)
+    if cols is None:
+        codes_o, exps_o, c_o, _ = oracle.pack_weight(W, G, mode)
+        assert np.array_equal(codes, codes_o) and np.array_equal(exps, exps_o) and bits_equal_f32(c, c_o)
+    else:
+        codes_o, exps_o, c_o, _ = oracle.pack_weight(np.ascontiguousarray(W[:, cols]), G, mode)
+        assert np.array_equal(codes[:, cols], codes_o) and np.array_equal(exps[:, cols], exps_o)
+        assert bits_equal_f32(c[cols], c_o)
+    return packed
+
+
+@pytest.mark.parametrize("G,mode", [(128, 1), (128, 2), (32, 1), (32, 2), (64, 1), (256, 2)])
+def test_packer_tiny_bit_exact(G, mode):
+    _pack_and_compare(inputs.make_w(CFG["tiny"]), G, mode)
+
+
+@pytest.mark.parametrize("K,N,G,mode", [(384, 200, 384, 1), (640, 37, 320, 2), (384, 16, 96, 1), (256, 1, 128, 2)])
+def test_packer_ragged_shapes_bit_exact(K, N, G, mode):
+    W = inputs.make_w(CFG["tiny"], K=K, N=N)
+    w = inputs.bf16_bits_to_f32(W).copy()
+    w[: G, 0] = 0.0                      # a zero group
+    w[3, -1] = 0.75; w[5, -1] = -0.375   # exact ties after scaling
+    if N > 20:
+        w[:, 20] *= 2.0 ** -120          # vanishing column
+        w[:, 19] *= 2.0 ** 100
+    _pack_and_compare(inputs.f32_to_bf16_bits(w), G, mode)
+
+
+@pytest.mark.parametrize("name", ["opt1p3b_fc1", "llama7b_ffn_up", "llama70b_ffn_decode"])
+def test_packer_full_size_sampled_columns(name):
+    cfg = CFG[name]
+    W = inputs.make_w(cfg)
+    rng = np.random.default_rng(1)
+    cols = np.sort(np.concatenate([rng.choice(cfg.N, 510, replace=False), [0, cfg.N - 1]]))
+    cols = np.unique(cols)
+    _pack_and_compare(W, cfg.G, cfg.mode, cols)
+
+
+# ------------------------------------------------------------------ GEMM
+_W_CACHE = {}
+
+
+def _weights(cfg, G, mode):
+    """W bits and the GPU-packed blob; the last configuration is kept so that
+    the full-size cases of one layer do not regenerate and repack it."""
+    key = (cfg.name, cfg.K, cfg.N, G, mode, cfg.seed)
+    if key not in _W_CACHE:
+        _W_CACHE.clear()
+        W = inputs.make_w(cfg)
+        _W_CACHE[key] = (W, zqfp.pack_weight_fp4(bf16_tensor(W), G, mode))
+    return _W_CACHE[key]
+
+
+def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096, out_dtype=torch.float32,
+               x_override=None):
+    cfg = CFG[seed_cfg]
+    cfg = inputs.Config(cfg.name, K, N, (M,), G, mode, cfg.outlier_frac, cfg.outlier_count, cfg.outlier_gain, r, cfg.seed)
+    X = inputs.make_x(cfg, M) if x_override is None else x_override
+    W, packed = _weights(cfg, G, mode)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    T = V = T_o = Vb = None
+    if r:
+        U, Vb = inputs.make_uv(cfg, rank=r)
+        T_o, _ = oracle.lorc_left(X, U)
+        Xq, sx, _T = zqfp.quantize_act_fp8(bf16_tensor(X), f16_tensor(U))
+        # the GEMM check is fed the oracle's T so that it does not depend on the T check
+        T, V = f32_tensor(T_o), f16_tensor(Vb)
+    else:
+        Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(X))
+    assert np.array_equal(_sync_np(Xq), Xq_o) and bits_equal_f32(_sync_np(sx), sx_o)
+    if r:
+        Y = zqfp.w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=out_dtype)
+    else:
+        Y = zqfp.w4a8_gemm(Xq, sx, packed, N, G, out_dtype=out_dtype)
+    Y = _sync_np(Y.float())
+    # oracle side: its own packing of the same W (bit-identical to the GPU's, checked by the packer tests)
+    if full:
+        codes_o, exps_o, c_o, _ = oracle.pack_weight(W, G, mode)
+        Y_o, Sabs = oracle.gemm(Xq_o, sx_o, codes_o, exps_o, c_o, G, T=T_o, V=Vb)
+        return Y, Y_o, Sabs
+    rng = np.random.default_rng(5)
+    ms = rng.integers(0, M, nsamples)
+    ns = rng.integers(0, N, nsamples)
+    ms[:4] = [0, M - 1, 0, M - 1]
+    ns[:4] = [0, N - 1, N - 1, 0]
+    cols = np.unique(ns)
+    codes_s, exps_s, c_s, _ = oracle.pack_weight(np.ascontiguousarray(W[:, cols]), G, mode)
+    ns_local = np.searchsorted(cols, ns)
+    Vs = None if Vb is None else np.ascontiguousarray(Vb[:, cols])
+    Y_o, Sabs = oracle.gemm_samples(Xq_o, sx_o, codes_s, exps_s, c_s, G, ms, ns_local, T=T_o, V=Vs)
+    return Y[ms, ns], Y_o, Sabs
+
+
+@pytest.mark.parametrize("M,K,N,G,mode,r", [
+    (16, 256, 256, 128, 1, 0),      # the tiny configuration
+    (16, 256, 256, 32, 2, 0),
+    (1, 256, 48, 64, 1, 0),
+    (5, 384, 200, 384, 1, 3),       # ragged N, one group per column, odd rank
+    (33, 640, 37, 320, 2, 0),       # group size that neither divides nor is a multiple of 128
+    (64, 1024, 272, 128, 1, 8),
+    (77, 512, 200, 128, 2, 8),      # tiled form, ragged M and N
+    (200, 1280, 400, 256, 2, 0),    # tiled form, several tiles each way
+    (129, 384, 130, 32, 1, 16),
+])
+def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
+    Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
+    check_gemm(Y, Y_o, Sabs, f"M{M} K{K} N{N} G{G} mode{mode} r{r}")
+
+
+def test_gemm_bf16_output():
+    Y, Y_o, Sabs = _gemm_case(40, 512, 96, 128, 1, 0, out_dtype=torch.bfloat16)
+    want = torch.from_numpy(Y_o).to(torch.bfloat16).float().numpy()
+    # the bf16 rounding of a value within tolerance of the oracle's: equal or one bf16 ulp apart
+    assert np.all(np.abs(Y - want) <= np.abs(want) * 2.0 ** -7 + 1e-30)
+    assert (Y == want).mean() > 0.99
+
+
+def test_gemm_zero_rows_and_signed_zeros():
+    cfg = CFG["tiny"]
+    x = inputs.bf16_bits_to_f32(inputs.make_x(cfg, 16)).copy()
+    x[3] = 0.0
+    x[7] = -0.0
+    Y, Y_o, Sabs = _gemm_case(16, 256, 256, 128, 1, 0, x_override=inputs.f32_to_bf16_bits(x))
+    assert np.all(Y[3] == 0) and np.all(Y[7] == 0)
+    check_gemm(Y, Y_o, Sabs + 1e-300)
+
+
+FULL = [
+    ("opt1p3b_fc1", 2048), ("llama7b_qkv", 1), ("llama7b_qkv", 16), ("llama7b_qkv", 256), ("llama7b_qkv", 4096),
+    ("llama7b_ffn_up", 1), ("llama7b_ffn_up", 16), ("llama7b_ffn_up", 256), ("llama7b_ffn_up", 4096),
+    ("llama13b_ffn_lorc", 16), ("llama13b_ffn_lorc", 2048),
+    ("llama70b_ffn_decode", 1), ("llama70b_ffn_decode", 4), ("llama70b_ffn_decode", 16), ("llama70b_ffn_decode", 64),
+]
+
+
+@pytest.mark.parametrize("name,M", FULL)
+def test_gemm_full_size_sampled_outputs(name, M):
+    """The benchmark configurations at full size, in the launch configuration
+    the benchmark times; the oracle computes 4096 sampled outputs one by one."""
+    cfg = CFG[name]
+    Y, Y_o, Sabs = _gemm_case(M, cfg.K, cfg.N, cfg.G, cfg.mode, cfg.rank, seed_cfg=name, full=False)
+    fro, ratio = check_gemm(Y, Y_o, Sabs, f"{name} M={M}")
+    print(f"{name} M={M}: rel-Frobenius {fro:.2e}, max|err|/sum|aw| {ratio:.2e}")
+
+
+# ------------------------------------------------------------------ accumulation modes
+def _all_exponent_x(M, K, seed=0):
+    """Rows drawn uniformly over all finite E4M3 codes (every exponent equally
+    likely, row maximum 448): the widest dynamic range the format allows inside
+    every run of 8 consecutive k."""
+    rng = np.random.default_rng(seed)
+    vals = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F])
+    x = vals[rng.choice(finite, (M, K))]
+    x[:, 0] = 448.0
+    return inputs.f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("M,K,N", [(16, 1024, 256), (96, 1024, 256)])
+def test_exact_mode_holds_the_bound_on_widest_dynamic_range(M, K, N):
+    X = _all_exponent_x(M, K)
+    Y, Y_o, Sabs = _gemm_case(M, K, N, 128, 1, 0, x_override=X)
+    fro, ratio = check_gemm(Y, Y_o, Sabs, "all-exponent rows, exact accumulation")
+    print(f"exact: rel-Fro {fro:.2e} ratio {ratio:.2e}")
+
+
+@pytest.mark.parametrize("M,K,N,seed_cfg", [(16, 256, 256, "tiny"), (16, 4096, 1024, "llama7b_qkv"),
+                                            (256, 4096, 1024, "llama70b_ffn_decode")])
+def test_fast_mode_meets_its_documented_bound(M, K, N, seed_cfg):
+    """One-pass accumulation is OUTSIDE the parity tolerance on activations with
+    outlier channels (the matrix core truncates products more than 8 binades
+    below the largest of their run of 8); its documented bounds are relative
+    Frobenius error <= 1e-4 and |err| <= 2^-10 * sum|a w|."""
+    cfg = CFG[seed_cfg]
+    cfg = inputs.Config(cfg.name, K, N, (M,), 128, 1, cfg.outlier_frac, cfg.outlier_count, cfg.outlier_gain, 0, cfg.seed)
+    X = inputs.make_x(cfg, M)
+    W, packed = _weights(cfg, 128, 1)
+    Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(X))
+    Y = _sync_np(zqfp.w4a8_gemm(Xq, sx, packed, N, 128, accum=zqfp.ACCUM_FAST))
+    Xq_o, sx_o = oracle.quantize_act(X)
+    codes_o, exps_o, c_o, _ = oracle.pack_weight(W, 128, 1)
+    Y_o, Sabs = oracle.gemm(Xq_o, sx_o, codes_o, exps_o, c_o, 128)
+    err = np.abs(Y.astype(np.float64) - Y_o)
+    fro = np.linalg.norm(Y - Y_o) / np.linalg.norm(Y_o)
+    ratio = (err / Sabs).max()
+    print(f"fast: rel-Fro {fro:.2e} ratio {ratio:.2e} (2^-18 = {2.0**-18:.2e})")
+    assert fro <= 1e-4 and ratio <= 2.0 ** -10

@@ -1,0 +1,81 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its argument checks reject bad calls before touching the
+GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2307_09782_amd import zqfp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "zqfp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zqfp_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(zqfp.LIB_PATH):
+        from paper_2307_09782_amd.build import build_lib
+        build_lib()
+    return zqfp.lib()
+
+
+def test_header_declares_the_four_calls_of_the_boundary():
+    syms = _declared_symbols()
+    for name in ("zqfp_quantize_act_fp8", "zqfp_pack_weight_fp4", "zqfp_w4a8_gemm", "zqfp_w4a8_gemm_lorc"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared_symbols():
+        assert hasattr(lib, name), name
+    assert lib.zqfp_version() >= 100
+
+
+def test_packed_size_and_shape_limits(lib):
+    # codes K*N/2 + exponents K/G*N + column scales 4N, plus header and padding
+    K, N, G = 4096, 12288, 128
+    n = lib.zqfp_packed_weight_bytes(K, N, G)
+    payload = K * N // 2 + (K // G) * N + 4 * N
+    assert payload + 256 <= n <= payload + 256 + 3 * 256
+    assert lib.zqfp_packed_weight_bytes(4096, 100, 128) > 0      # N need not be a multiple of 16
+    assert lib.zqfp_packed_weight_bytes(4000, 128, 128) == 0     # K % 128
+    assert lib.zqfp_packed_weight_bytes(4096, 128, 48) == 0      # G % 32
+    assert lib.zqfp_packed_weight_bytes(4096, 128, 96) == 0      # K % G
+    assert lib.zqfp_packed_weight_bytes(3200, 128, 320) > 0      # the paper's LLaMA-3b group size
+    assert lib.zqfp_packed_weight_bytes(32768, 128, 32) == 0     # K / G > 256
+    assert lib.zqfp_packed_weight_bytes(4096, 128, 256) > 0
+    assert lib.zqfp_packed_weight_bytes(4096, 128, 32) > 0
+    assert lib.zqfp_gemm_workspace_bytes(16, 4096, 4096) == 0
+
+
+def test_argument_checks_return_error_codes_without_a_gpu(lib):
+    p = ctypes.c_void_p
+    buf = (ctypes.c_uint8 * 4096)()
+    a = ctypes.addressof(buf)
+    a16 = (a + 255) // 256 * 256
+    # quantizer: K % 128, NULL pointers, alignment
+    assert lib.zqfp_quantize_act_fp8(p(a16), 1, 100, 100, p(a16), p(a16), None, 0, None, None) == -2
+    assert lib.zqfp_quantize_act_fp8(None, 1, 128, 128, p(a16), p(a16), None, 0, None, None) == -1
+    assert lib.zqfp_quantize_act_fp8(p(a16 + 2), 1, 128, 128, p(a16), p(a16), None, 0, None, None) == -3
+    assert lib.zqfp_quantize_act_fp8(p(a16), 1, 128, 128, p(a16), p(a16), None, 8, None, None) == -1
+    assert lib.zqfp_quantize_act_fp8(p(a16), 0, 128, 128, p(a16), p(a16), None, 0, None, None) == 0
+    # packer: mode, shape
+    assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 16, 128, 3, p(a16), None) == -4
+    assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 8, 128, 1, p(a16), None) == -2
+    assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 16, 128, 1, None, None) == -1
+    assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 16, 128, 1, p(a16 + 16), None) == -3
+    # gemm: out dtype, rank, empty problem is a no-op
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 7, 0, None, None) == -4
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 0, 5, None, None) == -4
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 0, 128, p(a16), 16, 128, p(a16), 16, 0, 0, None, None) == 0
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, None, 16, 128, p(a16), 16, 0, 0, None, None) == -1
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 8, 0, 0, None, None) == -2
+    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, None, None, 8, p(a16), 16, 0, 0, None, None) == -1
+    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), p(a16), 65, p(a16), 16, 0, 0, None, None) == -2
