@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 linear-layer hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input
+already resident in HBM: token-wise FP8 quantization of X (plus the LoRC left
+factor when the configuration has LoRC) followed by the W4A8 GEMM (with the
+fused LoRC epilogue).  The weight packing is offline and not part of a step.
+
+Prints ONE JSON line (see the keys below).  `value` is TFLOP/s of the step,
+2*M*K*N / step time; `roofline` prices the GEMM kernel alone against the FP8
+matrix-core peak (or HBM for decode-sized M), from HIP-event durations taken
+inside the timed loop; `cpu_baseline` is the CPU oracle timed on a bounded
+sample of the same workload; `also` lists the other shapes measured in the
+same run (decode shapes rotate through weight copies totalling > 512 MB so
+that the 256 MB last-level cache cannot serve them).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2307_09782_amd import inputs, zqfp  # noqa: E402
+
+METRIC = "W4A8 GEMM TFLOPS & HBM GB/s at LLaMA-7B/70B shapes; % FP8 MFMA/HBM roofline"
+PEAK_FP8_TFLOPS = 5000.0   # MI355X dense FP8 matrix-core peak
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def bf16_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def f16_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.float16).cuda()
+
+
+def algorithmic_bytes(cfg, M, out_bytes=4):
+    """Bytes the GEMM call itself must move once (packed codes + exponent bytes
+    + column scales + FP8 activations + token scales + output + LoRC factors)."""
+    K, N, G, r = cfg.K, cfg.N, cfg.G, cfg.rank
+    w = K * N // 2 + (K // G) * N + 4 * N
+    return w + M * K + 4 * M + out_bytes * M * N + (4 * M * r + 2 * r * N if r else 0)
+
+
+class Workload:
+    def __init__(self, name, M, accum, copies=1):
+        self.cfg = cfg = inputs.CONFIGS[name]
+        self.name, self.M, self.accum = name, M, accum
+        self.X = bf16_dev(inputs.make_x(cfg, M))
+        Wd = bf16_dev(inputs.make_w(cfg))
+        packed = zqfp.pack_weight_fp4(Wd, cfg.G, cfg.mode)
+        del Wd
+        self.packed = [packed] + [packed.clone() for _ in range(copies - 1)]
+        self.U = self.V = None
+        if cfg.rank:
+            U, V = inputs.make_uv(cfg)
+            self.U, self.V = f16_dev(U), f16_dev(V)
+        self.Y = torch.empty((M, cfg.N), dtype=torch.float32, device="cuda")
+        self.flops = 2.0 * M * cfg.K * cfg.N
+        self.bytes = algorithmic_bytes(cfg, M)
+        self.i = 0
+
+    def step(self, ev=None):
+        cfg = self.cfg
+        packed = self.packed[self.i % len(self.packed)]
+        self.i += 1
+        if cfg.rank:
+            Xq, sx, T = zqfp.quantize_act_fp8(self.X, self.U)
+            if ev: ev[0].record()
+            zqfp.w4a8_gemm_lorc(Xq, sx, packed, cfg.N, cfg.G, T, self.V, accum=self.accum, out=self.Y)
+            if ev: ev[1].record()
+        else:
+            Xq, sx = zqfp.quantize_act_fp8(self.X)
+            if ev: ev[0].record()
+            zqfp.w4a8_gemm(Xq, sx, packed, cfg.N, cfg.G, accum=self.accum, out=self.Y)
+            if ev: ev[1].record()
+
+    def run(self, steps, warmup):
+        for _ in range(warmup):
+            self.step()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            self.step(evs[k])
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        return dt * 1e3, gemm_ms
+
+    def gemm_graph_ms(self, replays=20):
+        """Average GEMM kernel time with launch gaps removed: one HIP graph holding
+        one GEMM launch per weight copy, replayed `replays` times."""
+        cfg = self.cfg
+        if cfg.rank:
+            Xq, sx, T = zqfp.quantize_act_fp8(self.X, self.U)
+        else:
+            Xq, sx = zqfp.quantize_act_fp8(self.X)
+
+        def launches():
+            for packed in self.packed:
+                if cfg.rank:
+                    zqfp.w4a8_gemm_lorc(Xq, sx, packed, cfg.N, cfg.G, T, self.V, accum=self.accum, out=self.Y)
+                else:
+                    zqfp.w4a8_gemm(Xq, sx, packed, cfg.N, cfg.G, accum=self.accum, out=self.Y)
+
+        launches()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            launches()
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(replays):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (replays * len(self.packed))
+
+    def summary(self, steps, warmup):
+        ms, gemm_ms = self.run(steps, warmup)
+        if self.M <= 64:  # kernels of a few microseconds: take launch gaps out of the per-kernel figure
+            gemm_ms = self.gemm_graph_ms()
+        tflops = self.flops / (gemm_ms * 1e-3) / 1e12
+        gbs = self.bytes / (gemm_ms * 1e-3) / 1e9
+        return {
+            "workload": f"{self.name} M={self.M}", "accum": "exact" if self.accum == 0 else "fast",
+            "ms_per_step": round(ms, 5), "gemm_ms": round(gemm_ms, 5),
+            "step_tflops": round(self.flops / (ms * 1e-3) / 1e12, 3),
+            "gemm_tflops": round(tflops, 3), "gemm_gbs": round(gbs, 1),
+            "frac_fp8_mfma_peak": round(tflops / PEAK_FP8_TFLOPS, 4), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+            "weight_copies_rotated": len(self.packed),
+        }
+
+
+def cpu_baseline(name, M, rows=8):
+    """The CPU oracle on a bounded sample: `rows` tokens of the same workload,
+    whole hot path (quantize, LoRC left factor, GEMM over all N)."""
+    import oracle
+    cfg = inputs.CONFIGS[name]
+    rows = min(rows, M)
+    X = inputs.make_x(cfg, M)[:rows].copy()
+    W = inputs.make_w(cfg)
+    codes, exps, c, _ = oracle.pack_weight(W, cfg.G, cfg.mode)  # offline, not timed
+    U = V = T = None
+    if cfg.rank:
+        U, V = inputs.make_uv(cfg)
+    t0 = time.perf_counter()
+    Xq, sx = oracle.quantize_act(X)
+    if cfg.rank:
+        T, _ = oracle.lorc_left(X, U)
+    oracle.gemm(Xq, sx, codes, exps, c, cfg.G, T=T, V=V, want_abs=False)
+    dt = time.perf_counter() - t0
+    threads = min(oracle.max_threads(), rows)
+    return {"value": round(2.0 * rows * cfg.K * cfg.N / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
+            "kind": "oracle", "sample": f"{rows} of {M} tokens, all {cfg.N} outputs, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama7b_qkv")
+    ap.add_argument("--M", type=int, default=4096)
+    ap.add_argument("--accum", choices=["exact", "fast"], default="exact")
+    ap.add_argument("--no-also", action="store_true", help="skip the extra shapes")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    zqfp.lib()  # fail loudly if the HIP library has not been built
+    accum = zqfp.ACCUM_EXACT if args.accum == "exact" else zqfp.ACCUM_FAST
+
+    main_wl = Workload(args.workload, args.M, accum)
+    ms, gemm_ms = main_wl.run(args.steps, args.warmup)
+    cfg = main_wl.cfg
+    value = main_wl.flops / (ms * 1e-3) / 1e12
+    gemm_tflops = main_wl.flops / (gemm_ms * 1e-3) / 1e12
+    out = {
+        "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3 x fp4_e2m1 -> f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload} M={args.M} K={cfg.K} N={cfg.N} G={cfg.G} "
+                               f"{'M1' if cfg.mode == 1 else 'M2'} rank={cfg.rank}",
+                   "accum": args.accum, "step": "quantize_act_fp8 + w4a8_gemm" + ("_lorc" if cfg.rank else "")},
+        "roofline": {"bound": "mfma", "achieved": round(gemm_tflops, 3), "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4), "traffic": None,
+                     "kernel": "k_gemm_tile", "kernel_ms": round(gemm_ms, 5)},
+    }
+    del main_wl
+    torch.cuda.empty_cache()
+
+    if not args.no_also:
+        also = []
+        plan = [
+            ("llama7b_qkv", 4096, zqfp.ACCUM_FAST, 1),
+            ("llama7b_ffn_up", 4096, accum, 1),
+            ("llama13b_ffn_lorc", 2048, accum, 1),
+            ("llama7b_qkv", 16, accum, 24),
+            ("llama70b_ffn_decode", 16, accum, 5),
+            ("llama70b_ffn_decode", 1, accum, 5),
+        ]
+        for name, M, acc, copies in plan:
+            wl = Workload(name, M, acc, copies)
+            also.append(wl.summary(max(10, args.steps), args.warmup))
+            del wl
+            torch.cuda.empty_cache()
+        out["also"] = also
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.workload, args.M)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -20,6 +20,7 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
     const int64_t m_base = (int64_t)blockIdx.y * (16 * MT);
     const int nkt = (int)L.nkt;
 
-    const uint4* bfrag = reinterpret_cast<const uint4*>(blob + L.off_codes) + strip * nkt * 64 + lane;
+    const u32x4* bfrag = reinterpret_cast<const u32x4*>(blob + L.off_codes) + strip * nkt * 64 + lane;
     const uint32_t* ex = reinterpret_cast<const uint32_t*>(blob + L.off_exps) + strip * L.ngq * 16 + col;
 
     // A operand of the instruction: lane (row = lane%16, lb = lane/16) holds the bytes
@@ -63,9 +64,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
     for (int t = 0; t < MT; ++t) acc[t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     for (int kt0 = wave; kt0 < nkt; kt0 += kWaves * kUnroll) {
-        uint4 b[kUnroll];
+        u32x4 b[kUnroll];
         uint32_t e[kUnroll];
-        uint4 a_lo[kUnroll][MT], a_hi[kUnroll][MT];
+        u32x4 a_lo[kUnroll][MT], a_hi[kUnroll][MT];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int kt = kt0 + u * kWaves;
@@ -77,11 +78,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
                     if (alive[t]) {
-                        a_lo[u][t] = *reinterpret_cast<const uint4*>(arow[t] + (int64_t)kt * 128);
-                        a_hi[u][t] = *reinterpret_cast<const uint4*>(arow[t] + (int64_t)kt * 128 + 64);
+                        a_lo[u][t] = *reinterpret_cast<const u32x4*>(arow[t] + (int64_t)kt * 128);
+                        a_hi[u][t] = *reinterpret_cast<const u32x4*>(arow[t] + (int64_t)kt * 128 + 64);
                     } else {
-                        a_lo[u][t] = make_uint4(0, 0, 0, 0);
-                        a_hi[u][t] = make_uint4(0, 0, 0, 0);
+                        a_lo[u][t] = (u32x4){0u, 0u, 0u, 0u};
+                        a_hi[u][t] = (u32x4){0u, 0u, 0u, 0u};
                     }
                 }
             }
@@ -90,11 +91,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
         for (int u = 0; u < kUnroll; ++u) {
             const int kt = kt0 + u * kWaves;
             if (kt < nkt) {
-                v8i bv = {(int)b[u].x, (int)b[u].y, (int)b[u].z, (int)b[u].w, 0, 0, 0, 0};
+                v8i bv = {(int)b[u][0], (int)b[u][1], (int)b[u][2], (int)b[u][3], 0, 0, 0, 0};
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    v8i av = {(int)a_lo[u][t].x, (int)a_lo[u][t].y, (int)a_lo[u][t].z, (int)a_lo[u][t].w,
-                              (int)a_hi[u][t].x, (int)a_hi[u][t].y, (int)a_hi[u][t].z, (int)a_hi[u][t].w};
+                    v8i av = {(int)a_lo[u][t][0], (int)a_lo[u][t][1], (int)a_lo[u][t][2], (int)a_lo[u][t][3],
+                              (int)a_hi[u][t][0], (int)a_hi[u][t][1], (int)a_hi[u][t][2], (int)a_hi[u][t][3]};
                     // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
                     if constexpr (EXACT) {
                         v8i hi, lo;

@@ -3,17 +3,20 @@
 //
 //   Y[m,n] = (sx[m] c[n]) * sum_k a[m,k] * q[k,n] * 2^e[g(k),n]   (+ T.V, LoRC)
 //
-// (paper Sections 1 and 3.)  A workgroup of 4 waves (2 x 2) owns a BM x BN
-// output tile; each wave owns WTM x WTN tiles of 16 x 16 and walks K in steps
-// of 128 with v_mfma_scale_f32_16x16x128_f8f6f4 (A = E4M3 from LDS, B = packed
-// E2M1 from LDS, B's E8M0 group exponent straight from global memory into the
-// instruction's scale operand -- the FP4 -> FP8 alignment is done by the
-// matrix core, no unpack and no multiply).
+// (paper Sections 1 and 3.)  A workgroup of WAVES_M x WAVES_N waves owns a
+// BM x BN output tile; each wave owns WTM x WTN tiles of 16 x 16 and walks K in
+// steps of 128 with v_mfma_scale_f32_16x16x128_f8f6f4 (A = E4M3 from LDS,
+// B = packed E2M1 from LDS, B's E8M0 group exponent straight from global
+// memory into the instruction's scale operand -- the FP4 -> FP8 alignment is
+// done by the matrix core, no unpack and no multiply).
 //
-// LDS holds two stages.  A stage keeps the activation tile in "fragment order"
-// (per 16-row sub-tile: 2 halves x 64 lanes x 16 B, lane = 16*(k/16 % 4) + row)
-// so that every operand read is a conflict-free 16 B/lane read; the weight
-// tile already has that order in memory and is copied as is.
+// Two waves share a SIMD so that one wave's LDS reads and barrier waits hide
+// behind the other's matrix instructions.  LDS holds two stages; the next
+// stage travels global -> registers during the current step's matrix work and
+// registers -> LDS at its end.  A stage keeps the activation tile in "fragment
+// order" (per 16-row sub-tile: 2 halves x 64 lanes x 16 B, lane = 16*(k/16 % 4)
+// + row) so that every operand read is a conflict-free 16 B/lane read; the
+// weight tile already has that order in memory and is copied as is.
 #include "zqfp_internal.h"
 
 namespace zqfp {
@@ -21,8 +24,7 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline uint16_t f32_to_bf16_bits(float f)
 {
@@ -31,22 +33,26 @@ __device__ inline uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
-template <int WTM, int WTN>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N>
 struct TileCfg {
-    static constexpr int BM = 2 * WTM * 16, BN = 2 * WTN * 16;
+    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int BM = WAVES_M * WTM * 16, BN = WAVES_N * WTN * 16;
     static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 64;
-    static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int A_CHUNKS = A_BYTES / 16 / kThreads;  // 16 B chunks per thread
-    static constexpr int B_CHUNKS = B_BYTES / 16 / kThreads;
+    static constexpr int E_BYTES = THREADS * 4;               // one exponent dword per output channel (first BN used)
+    static constexpr int STAGE = A_BYTES + B_BYTES + E_BYTES;
+    static constexpr int A_CHUNKS = A_BYTES / 16 / THREADS;  // 16 B chunks per thread
+    static constexpr int B_CHUNKS = B_BYTES / 16 / THREADS;
+    static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile / thread mismatch");
+    static_assert(BN <= THREADS, "one exponent dword per thread");
 };
 
-template <int WTM, int WTN, bool EXACT>
-__global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restrict__ Xq, const float* __restrict__ sx,
-                                                      int64_t M, const uint8_t* __restrict__ blob, BlobLayout L, Lorc lorc,
-                                                      void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m,
-                                                      int tiles_n)
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_gemm_tile(
+    const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
+    BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n)
 {
-    using C = TileCfg<WTM, WTN>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
+    constexpr int kThreads = C::THREADS;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- workgroup -> tile.  Consecutive workgroup ids go to consecutive XCDs (8 of them, one
@@ -57,8 +63,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
     {
         const int per = (ntiles + 7) / 8;
         const int xcd = pid & 7, loc = pid >> 3;
-        int id = xcd * per + loc;
-        if (id >= ntiles || loc >= per) return;
+        const int id = xcd * per + loc;
+        if (id >= ntiles) return;
         pid = id;
     }
     constexpr int GROUP_M = 8;
@@ -70,58 +76,74 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
     const int tn = (pid % in_group) / gsz;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int col = lane & 15, lb = lane >> 4;
     const int64_t m0 = (int64_t)tm * C::BM;
     const int64_t strip0 = (int64_t)tn * (C::BN / 16);
     const int nkt = (int)L.nkt;
 
-    const uint8_t* codes = blob + L.off_codes;
-    const uint32_t* exq = reinterpret_cast<const uint32_t*>(blob + L.off_exps);
+    // ---- staging addresses: uniform base pointers plus small per-thread offsets.  Rows past M
+    // and strips past the last one are clamped to the last valid one: what they produce is
+    // never stored.
+    const uint8_t* a_base = Xq + m0 * L.K;                    // uniform
+    const uint8_t* b_base = blob + L.off_codes;               // uniform
+    const uint32_t* e_base = reinterpret_cast<const uint32_t*>(blob + L.off_exps);
+    const int rows_here = (int)min((int64_t)C::BM, M - m0);   // >= 1
+    uint32_t a_off[C::A_CHUNKS], b_off[C::B_CHUNKS];
+    const int a_dst0 = (tid >> 7) * 2048 + ((tid >> 6) & 1) * 1024 + (((tid >> 4) & 3) * 16 + (tid & 15)) * 16;
+#pragma unroll
+    for (int i = 0; i < C::A_CHUNKS; ++i) {
+        const int cidx = tid + kThreads * i;
+        const int r = cidx & 15, j = (cidx >> 4) & 7, sub = cidx >> 7;
+        a_off[i] = (uint32_t)(min(sub * 16 + r, rows_here - 1) * (int)L.K + 16 * j);
+    }
+#pragma unroll
+    for (int i = 0; i < C::B_CHUNKS; ++i) {
+        const int cidx = tid + kThreads * i;
+        const int64_t strip = min(strip0 + (cidx >> 6), L.nstrips - 1);
+        b_off[i] = (uint32_t)((strip * nkt * 64 + (cidx & 63)) * 16);
+    }
+    // exponent dwords, [strip][quad][column] in memory: thread t < BN stages the dword of
+    // column t of the tile; it lands in LDS as [column] and every lane later picks its own.
+    // (Threads past BN stage a duplicate into padding: the loop body stays free of branches.)
+    const uint32_t e_off = (uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15);
 
-    // ---- global -> register staging
-    uint4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
-    uint32_t re[WTN], e_cur[WTN];
+    // stored exponent group of 32-block `b` of k-tile kt.  Stored groups are 32 or 64 wide (then
+    // a shift does it) or a multiple of 128 (then all four blocks share group kt / (gsb / 4), which
+    // the loop tracks with a counter instead of dividing).
+    const bool small_groups = L.gsb < 4;
+    const int gq = max(1, L.gsb >> 2);
+    int big_group_of[2] = {0, 0};  // [kt & 1]: group of k-tile kt for groups >= 128
+    int big_sub = 0;
+    auto stored_group = [&](int kt, int b) {
+        return small_groups ? ((kt * 4 + b) >> L.gsb_shift) : big_group_of[kt & 1];
+    };
+    auto advance_group = [&](int kt_next) {  // call before touching k-tile kt_next (in order)
+        int g = big_group_of[(kt_next - 1) & 1];
+        if (++big_sub == gq) { big_sub = 0; ++g; }
+        big_group_of[kt_next & 1] = g;
+    };
+
+    u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
+    uint32_t re = 0;
 
     auto gload = [&](int kt) {
 #pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i) {
-            const int cidx = tid + kThreads * i;
-            const int r = cidx & 15, j = (cidx >> 4) & 7, sub = cidx >> 7;
-            const int64_t m = m0 + sub * 16 + r;
-            ra[i] = (m < M) ? *reinterpret_cast<const uint4*>(Xq + m * L.K + (int64_t)kt * 128 + 16 * j)
-                            : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < C::A_CHUNKS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_base + a_off[i] + kt * 128);
 #pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i) {
-            const int cidx = tid + kThreads * i;
-            const int64_t strip = strip0 + (cidx >> 6);
-            rb[i] = (strip < L.nstrips)
-                        ? *reinterpret_cast<const uint4*>(codes + ((strip * nkt + kt) * 64 + (cidx & 63)) * 16)
-                        : make_uint4(0, 0, 0, 0);
-        }
-        const int blk = kt * 4 + lb;
-        const int sg = (L.gsb_shift >= 0) ? (blk >> L.gsb_shift) : (blk / L.gsb);
-#pragma unroll
-        for (int j = 0; j < WTN; ++j) {
-            const int64_t strip = strip0 + wn * WTN + j;
-            re[j] = (strip < L.nstrips) ? (exq[(strip * L.ngq + (sg >> 2)) * 16 + col] >> (8 * (sg & 3))) : 127u;
-        }
+        for (int i = 0; i < C::B_CHUNKS; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_base + b_off[i] + kt * 1024);
+        // the dword holds 4 stored groups; the four 32-blocks of a k-tile always fall into one dword
+        // (groups of 32 or 64: the k-tile starts at a multiple of 4 blocks; larger groups: one group)
+        re = e_base[e_off + (stored_group(kt, 0) >> 2) * 16];
     };
     auto lstore = [&](int stage) {
-        uint8_t* sa = smem + stage * C::STAGE;
-        uint8_t* sb = sa + C::A_BYTES;
+        uint8_t* sa = smem + stage * C::STAGE + a_dst0;
+        uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + tid * 16;
 #pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i) {
-            const int cidx = tid + kThreads * i;
-            const int r = cidx & 15, j = (cidx >> 4) & 7, sub = cidx >> 7;
-            *reinterpret_cast<uint4*>(sa + sub * 2048 + (j >> 2) * 1024 + ((j & 3) * 16 + r) * 16) = ra[i];
-        }
+        for (int i = 0; i < C::A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(sa + i * (kThreads / 128) * 2048) = ra[i];
 #pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i) {
-            const int cidx = tid + kThreads * i;
-            *reinterpret_cast<uint4*>(sb + cidx * 16) = rb[i];
-        }
+        for (int i = 0; i < C::B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(sb + i * kThreads * 16) = rb[i];
+        *reinterpret_cast<uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES + tid * 4) = re;
     };
 
     v4f acc[WTM][WTN];
@@ -132,27 +154,36 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
 
     gload(0);
     lstore(0);
-#pragma unroll
-    for (int j = 0; j < WTN; ++j) e_cur[j] = re[j];
     __syncthreads();
 
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int stage = kt & 1;
-        if (kt + 1 < nkt) gload(kt + 1);
-
+    auto compute = [&](int kt, int stage) {
         const uint8_t* sa = smem + stage * C::STAGE + (wm * WTM) * 2048 + lane * 16;
         const uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
+        // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
+        const uint32_t* se = reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) +
+                             wn * WTN * 16 + col;
+        const int esh = 8 * (stored_group(kt, lb) & 3);
         v8i bfr[WTN];
+        uint32_t e_cur[WTN];
 #pragma unroll
         for (int j = 0; j < WTN; ++j) {
-            uint4 b = *reinterpret_cast<const uint4*>(sb + j * 1024);
-            bfr[j] = (v8i){(int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0};
+            const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
+            bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+            e_cur[j] = se[j * 16] >> esh;
         }
+        // activation fragments are read one step ahead of the matrix instructions that use
+        // them; the scheduling fences keep the compiler from hoisting all of them (and the
+        // stores to the other LDS stage) above the matrix work
+        u32x4 a0 = *reinterpret_cast<const u32x4*>(sa);
+        u32x4 a1 = *reinterpret_cast<const u32x4*>(sa + 1024);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < WTM; ++i) {
-            uint4 lo = *reinterpret_cast<const uint4*>(sa + i * 2048);
-            uint4 hi = *reinterpret_cast<const uint4*>(sa + i * 2048 + 1024);
-            v8i afr = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            v8i afr = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+            if (i + 1 < WTM) {
+                a0 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048);
+                a1 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + 1024);
+            }
             if constexpr (EXACT) {
                 v8i hi, lo;
                 split_exponent_bands(afr, hi, lo);
@@ -170,15 +201,24 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
                                                                                   (int)e_cur[j]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 
-        if (kt + 1 < nkt) {
-            lstore(stage ^ 1);
-#pragma unroll
-            for (int j = 0; j < WTN; ++j) e_cur[j] = re[j];
-        }
+    };
+
+    // all steps but the last: fetch the next stage while computing this one (no branches in the
+    // loop body, so that the stores to the other stage stay behind the matrix work)
+    for (int kt = 0; kt + 1 < nkt; ++kt) {
+        const int stage = kt & 1;
+        advance_group(kt + 1);
+        gload(kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(kt, stage);
+        __builtin_amdgcn_sched_barrier(0);
+        lstore(stage ^ 1);
         __syncthreads();
     }
+    compute(nkt - 1, (nkt - 1) & 1);
 
     // ---- epilogue: D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
@@ -188,7 +228,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
         if (n >= L.N) continue;
         const float cn = colscale[n];
         float v[8];
-        for (int q = 0; q < lorc.r && q < 8; ++q) v[q] = half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = (q < lorc.r) ? half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]) : 0.f;
 #pragma unroll
         for (int i = 0; i < WTM; ++i) {
 #pragma unroll
@@ -199,7 +240,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
                 if (lorc.r > 0) {
                     const float* t = lorc.T + m * lorc.r;
                     if (lorc.r <= 8) {
-                        for (int q = 0; q < lorc.r; ++q) y = fmaf(t[q], v[q], y);
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            if (q < lorc.r) y = fmaf(t[q], v[q], y);
                     } else {
                         for (int q = 0; q < lorc.r; ++q)
                             y = fmaf(t[q], half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]), y);
@@ -212,16 +255,16 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tile(const uint8_t* __restric
     }
 }
 
-template <int WTM, int WTN, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                       void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
-    using C = TileCfg<WTM, WTN>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
     const int ntiles = tiles_m * tiles_n;
     const int per = (ntiles + 7) / 8;
     const size_t smem = 2 * C::STAGE;
-    auto kern = k_gemm_tile<WTM, WTN, EXACT>;
+    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, EXACT>;
     static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -229,9 +272,19 @@ hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(kThreads), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(C::THREADS), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy,
                        out_dtype, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+template <bool EXACT>
+hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
+                       void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+{
+    // 256 x 256 tiles once they fill the 256 compute units at least ~twice, else 128 x 128
+    const int64_t big = ((M + 255) / 256) * ((L.Np + 255) / 256);
+    if (big >= 384) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
 }
 
 }  // namespace
@@ -241,8 +294,8 @@ bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 64 && L.N 
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
                             Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
 {
-    return accum == 0 ? launch_cfg<4, 4, true>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s)
-                      : launch_cfg<4, 4, false>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    return accum == 0 ? launch_pick<true>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s)
+                      : launch_pick<false>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
 }
 
 }  // namespace zqfp
