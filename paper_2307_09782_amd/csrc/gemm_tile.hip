@@ -46,8 +46,10 @@ struct TileCfg {
     static_assert(BN <= THREADS, "one exponent dword per thread");
 };
 
+// Two waves per SIMD in every configuration (8-wave workgroups alone on a compute unit, 4-wave
+// workgroups in pairs): 256 registers per lane.
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_gemm_tile(
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
     BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n)
 {
@@ -220,36 +222,70 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_gemm_tile(
     }
     compute(nkt - 1, (nkt - 1) & 1);
 
-    // ---- epilogue: D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4
+    // ---- epilogue.  D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4:
+    // good for the scale / LoRC arithmetic (one column per lane), bad for stores (64 B runs).
+    // Each wave therefore passes its 16 x (16*WTN) slabs through a private LDS patch (row stride
+    // 16*WTN + 4 floats: the four row groups of a store land on disjoint banks, rows stay 16 B
+    // aligned) and writes them out as 16 B per lane, whole rows of the slab at a time.
+    constexpr int SLAB_N = 16 * WTN, SLAB_LD = SLAB_N + 4;
+    static_assert(C::THREADS / 64 * 16 * SLAB_LD * 4 <= 2 * C::STAGE, "epilogue patch does not fit the stages");
+    __syncthreads();  // every wave is done reading the stages
+    float* patch = reinterpret_cast<float*>(smem) + wave * (16 * SLAB_LD);
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
+    const int64_t n_wave = (strip0 + wn * WTN) * 16;
+    float cn[WTN];
 #pragma unroll
-    for (int j = 0; j < WTN; ++j) {
-        const int64_t n = (strip0 + wn * WTN + j) * 16 + col;
-        if (n >= L.N) continue;
-        const float cn = colscale[n];
-        float v[8];
+    for (int j = 0; j < WTN; ++j) cn[j] = colscale[min(n_wave + j * 16 + col, L.Np - 1)];
+    constexpr int LPR = SLAB_N / 4;   // lanes per slab row when each lane carries 4 columns
+    constexpr int RPI = 64 / LPR;     // slab rows per store instruction
+    const int srow = lane / LPR, scol = (lane % LPR) * 4;
+    const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = (q < lorc.r) ? half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]) : 0.f;
+    for (int i = 0; i < WTM; ++i) {
+        const int64_t m_slab = m0 + (wm * WTM + i) * 16;
+        float sxm[4];
 #pragma unroll
-        for (int i = 0; i < WTM; ++i) {
+        for (int rg = 0; rg < 4; ++rg) sxm[rg] = sx[min(m_slab + 4 * lb + rg, M - 1)];
+#pragma unroll
+        for (int j = 0; j < WTN; ++j) {
+            const int64_t n = min(n_wave + j * 16 + col, L.N - 1);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
-                const int64_t m = m0 + (wm * WTM + i) * 16 + 4 * lb + rg;
-                if (m >= M) continue;
-                float y = (sx[m] * cn) * acc[i][j][rg];
+                float y = (sxm[rg] * cn[j]) * acc[i][j][rg];
                 if (lorc.r > 0) {
-                    const float* t = lorc.T + m * lorc.r;
-                    if (lorc.r <= 8) {
-#pragma unroll
-                        for (int q = 0; q < 8; ++q)
-                            if (q < lorc.r) y = fmaf(t[q], v[q], y);
-                    } else {
-                        for (int q = 0; q < lorc.r; ++q)
-                            y = fmaf(t[q], half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]), y);
-                    }
+                    const float* t = lorc.T + min(m_slab + 4 * lb + rg, M - 1) * lorc.r;
+                    for (int q = 0; q < lorc.r; ++q) y = fmaf(t[q], half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]), y);
                 }
-                if (out_dtype == 0) reinterpret_cast<float*>(Y)[m * ldy + n] = y;
-                else reinterpret_cast<uint16_t*>(Y)[m * ldy + n] = f32_to_bf16_bits(y);
+                patch[(4 * lb + rg) * SLAB_LD + j * 16 + col] = y;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 16 / RPI; ++t) {
+            const int r = t * RPI + srow;
+            const v4f y = *reinterpret_cast<const v4f*>(patch + r * SLAB_LD + scol);
+            const int64_t m = m_slab + r, n = n_wave + scol;
+            if (m >= M || n >= L.N) continue;
+            if (out_dtype == 0) {
+                float* dst = reinterpret_cast<float*>(Y) + m * ldy + n;
+                if (vec_ok && n + 3 < L.N) {
+                    *reinterpret_cast<v4f*>(dst) = y;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (n + q < L.N) dst[q] = y[q];
+                }
+            } else {
+                uint16_t* dst = reinterpret_cast<uint16_t*>(Y) + m * ldy + n;
+                if (vec_ok && n + 3 < L.N) {
+                    uint2 pk;
+                    pk.x = (uint32_t)f32_to_bf16_bits(y[0]) | ((uint32_t)f32_to_bf16_bits(y[1]) << 16);
+                    pk.y = (uint32_t)f32_to_bf16_bits(y[2]) | ((uint32_t)f32_to_bf16_bits(y[3]) << 16);
+                    *reinterpret_cast<uint2*>(dst) = pk;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (n + q < L.N) dst[q] = f32_to_bf16_bits(y[q]);
+                }
             }
         }
     }
