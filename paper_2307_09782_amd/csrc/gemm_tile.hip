@@ -110,42 +110,42 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // (Threads past BN stage a duplicate into padding: the loop body stays free of branches.)
     const uint32_t e_off = (uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15);
 
-    // stored exponent group of 32-block `b` of k-tile kt.  Stored groups are 32 or 64 wide (then
-    // a shift does it) or a multiple of 128 (then all four blocks share group kt / (gsb / 4), which
-    // the loop tracks with a counter instead of dividing).
+    // stored exponent group of a 32-block.  Stored groups are 32 or 64 wide (then a shift of the
+    // block index does it) or a multiple of 128 (then all four blocks of k-tile kt share group
+    // kt / (gsb / 4), which a cursor tracks with a counter instead of dividing).  One cursor follows
+    // the k-tile being computed, one the k-tile being fetched.
+    struct GroupCursor { int g, sub; };
     const bool small_groups = L.gsb < 4;
     const int gq = max(1, L.gsb >> 2);
-    int big_group_of[2] = {0, 0};  // [kt & 1]: group of k-tile kt for groups >= 128
-    int big_sub = 0;
-    auto stored_group = [&](int kt, int b) {
-        return small_groups ? ((kt * 4 + b) >> L.gsb_shift) : big_group_of[kt & 1];
+    auto group_of = [&](const GroupCursor& c, int kt, int b) {
+        return small_groups ? ((kt * 4 + b) >> L.gsb_shift) : c.g;
     };
-    auto advance_group = [&](int kt_next) {  // call before touching k-tile kt_next (in order)
-        int g = big_group_of[(kt_next - 1) & 1];
-        if (++big_sub == gq) { big_sub = 0; ++g; }
-        big_group_of[kt_next & 1] = g;
+    auto advance = [&](GroupCursor& c, bool moved) {
+        const int sub = c.sub + (moved ? 1 : 0);
+        const bool wrap = sub == gq;
+        c.sub = wrap ? 0 : sub;
+        c.g += wrap ? 1 : 0;
     };
 
+    // ---- register staging of one stage: A_CHUNKS + B_CHUNKS 16-byte chunks and one exponent dword
     u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
     uint32_t re = 0;
-
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_base + a_off[i] + kt * 128);
-#pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_base + b_off[i] + kt * 1024);
-        // the dword holds 4 stored groups; the four 32-blocks of a k-tile always fall into one dword
-        // (groups of 32 or 64: the k-tile starts at a multiple of 4 blocks; larger groups: one group)
-        re = e_base[e_off + (stored_group(kt, 0) >> 2) * 16];
+    constexpr int NSIDE = C::A_CHUNKS + C::B_CHUNKS + 1;
+    // t-th global load of k-tile kt into the staging registers
+    auto side_load = [&](int t, int kt, const GroupCursor& c) {
+        if (t < C::A_CHUNKS) ra[t] = *reinterpret_cast<const u32x4*>(a_base + a_off[t] + kt * 128);
+        else if (t < C::A_CHUNKS + C::B_CHUNKS)
+            rb[t - C::A_CHUNKS] = *reinterpret_cast<const u32x4*>(b_base + b_off[t - C::A_CHUNKS] + kt * 1024);
+        else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
+            re = e_base[e_off + (group_of(c, kt, 0) >> 2) * 16];
     };
-    auto lstore = [&](int stage) {
-        uint8_t* sa = smem + stage * C::STAGE + a_dst0;
-        uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + tid * 16;
-#pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(sa + i * (kThreads / 128) * 2048) = ra[i];
-#pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(sb + i * kThreads * 16) = rb[i];
-        *reinterpret_cast<uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES + tid * 4) = re;
+    // t-th store of the staging registers into LDS stage `stage`
+    auto side_store = [&](int t, int stage) {
+        uint8_t* st = smem + stage * C::STAGE;
+        if (t < C::A_CHUNKS) *reinterpret_cast<u32x4*>(st + a_dst0 + t * (kThreads / 128) * 2048) = ra[t];
+        else if (t < C::A_CHUNKS + C::B_CHUNKS)
+            *reinterpret_cast<u32x4*>(st + C::A_BYTES + tid * 16 + (t - C::A_CHUNKS) * kThreads * 16) = rb[t - C::A_CHUNKS];
+        else *reinterpret_cast<uint32_t*>(st + C::A_BYTES + C::B_BYTES + tid * 4) = re;
     };
 
     v4f acc[WTM][WTN];
@@ -154,73 +154,82 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
 #pragma unroll
         for (int j = 0; j < WTN; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    gload(0);
-    lstore(0);
+    // ---- prologue: k-tile 0 into stage 0, k-tile 1 into the staging registers
+    GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
+#pragma unroll
+    for (int t = 0; t < NSIDE; ++t) side_load(t, 0, cur_load);
+#pragma unroll
+    for (int t = 0; t < NSIDE; ++t) side_store(t, 0);
+    int kt_load = min(1, nkt - 1);
+    advance(cur_load, kt_load != 0);
+#pragma unroll
+    for (int t = 0; t < NSIDE; ++t) side_load(t, kt_load, cur_load);
     __syncthreads();
 
-    auto compute = [&](int kt, int stage) {
+    // ---- main loop.  In-order issue means that whatever a wave puts between two matrix
+    // instructions runs in the shadow of the matrix pipe, and whatever it puts after the last one
+    // waits for all of them.  So the stores of the staged k-tile (kt + 1) into the other LDS stage
+    // and the loads of k-tile kt + 2 are dealt out one per matrix instruction, and the scheduling
+    // fences pin that order.  Past the end the loads are clamped to the last k-tile (valid memory,
+    // never used): the loop body has no branches.
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int stage = kt & 1;
+        const int kt_next = min(kt_load + 1, nkt - 1);
+        GroupCursor cur_next = cur_load;
+        advance(cur_next, kt_next != kt_load);
+
         const uint8_t* sa = smem + stage * C::STAGE + (wm * WTM) * 2048 + lane * 16;
         const uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
         // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
         const uint32_t* se = reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) +
                              wn * WTN * 16 + col;
-        const int esh = 8 * (stored_group(kt, lb) & 3);
+        const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);
+        // LDS answers in order: exponents and the first fragments first, so that the first matrix
+        // instruction can start while the other weight fragments are still arriving
         v8i bfr[WTN];
         uint32_t e_cur[WTN];
 #pragma unroll
-        for (int j = 0; j < WTN; ++j) {
-            const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
-            bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
-            e_cur[j] = se[j * 16] >> esh;
-        }
-        // activation fragments are read one step ahead of the matrix instructions that use
-        // them; the scheduling fences keep the compiler from hoisting all of them (and the
-        // stores to the other LDS stage) above the matrix work
+        for (int j = 0; j < WTN; ++j) e_cur[j] = se[j * 16] >> esh;
         u32x4 a0 = *reinterpret_cast<const u32x4*>(sa);
         u32x4 a1 = *reinterpret_cast<const u32x4*>(sa + 1024);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
+        for (int j = 0; j < WTN; ++j) {
+            const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
+            bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
         for (int i = 0; i < WTM; ++i) {
             v8i afr = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
-            if (i + 1 < WTM) {
+            if (i + 1 < WTM) {  // next activation fragment, one block of matrix instructions ahead
                 a0 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048);
                 a1 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + 1024);
             }
-            if constexpr (EXACT) {
-                v8i hi, lo;
-                split_exponent_bands(afr, hi, lo);
-#pragma unroll
-                for (int j = 0; j < WTN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
-                                                                                  (int)e_cur[j]);
-#pragma unroll
-                for (int j = 0; j < WTN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lo, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
-                                                                                  (int)e_cur[j]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < WTN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
-                                                                                  (int)e_cur[j]);
-            }
+            v8i hi, lo;
+            if constexpr (EXACT) split_exponent_bands(afr, hi, lo);
             __builtin_amdgcn_sched_barrier(0);
+            constexpr int PASSES = EXACT ? 2 : 1;
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+#pragma unroll
+                for (int j = 0; j < WTN; ++j) {
+                    const v8i& op = EXACT ? (p == 0 ? hi : lo) : afr;
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
+                                                                                  (int)e_cur[j]);
+                    const int t = (i * PASSES + p) * WTN + j;  // position in the step's matrix-instruction stream
+                    if (t < NSIDE) side_store(t, stage ^ 1);
+                    else if (t < 2 * NSIDE) side_load(t - NSIDE, kt_next, cur_next);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
-
-    };
-
-    // all steps but the last: fetch the next stage while computing this one (no branches in the
-    // loop body, so that the stores to the other stage stay behind the matrix work)
-    for (int kt = 0; kt + 1 < nkt; ++kt) {
-        const int stage = kt & 1;
-        advance_group(kt + 1);
-        gload(kt + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(kt, stage);
-        __builtin_amdgcn_sched_barrier(0);
-        lstore(stage ^ 1);
+        static_assert(WTM * WTN >= 2 * NSIDE, "not enough matrix instructions to carry the staging traffic");
+        kt_load = kt_next;
+        cur_load = cur_next;
+        advance(cur_comp, true);
         __syncthreads();
     }
-    compute(nkt - 1, (nkt - 1) & 1);
 
     // ---- epilogue.  D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4:
     // good for the scale / LoRC arithmetic (one column per lane), bad for stores (64 B runs).
