@@ -142,7 +142,27 @@ class Workload:
         }
 
 
-def cpu_baseline(name, M, rows=8):
+def measured_traffic(workload_key):
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter runs (profiles/hbm_traffic.json,
+    written from FETCH_SIZE / WRITE_SIZE calibrated on a copy of known size); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    return json.load(open(path)).get(workload_key)
+
+
+def calibration_copy(nbytes=1 << 30):
+    """A plain device-to-device copy of known size: the yardstick for the HBM byte counters."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+    torch.cuda.empty_cache()
+
+
+def cpu_baseline(name, M, rows=2048):
     """The CPU oracle on a bounded sample: `rows` tokens of the same workload,
     whole hot path (quantize, LoRC left factor, GEMM over all N)."""
     import oracle
@@ -175,6 +195,8 @@ def main():
     ap.add_argument("--accum", choices=["exact", "fast"], default="exact")
     ap.add_argument("--no-also", action="store_true", help="skip the extra shapes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (yardstick for rocprofv3 HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)")
@@ -183,6 +205,8 @@ def main():
     zqfp.lib()  # fail loudly if the HIP library has not been built
     accum = zqfp.ACCUM_EXACT if args.accum == "exact" else zqfp.ACCUM_FAST
 
+    if args.calib_copy:
+        calibration_copy()
     main_wl = Workload(args.workload, args.M, accum)
     ms, gemm_ms = main_wl.run(args.steps, args.warmup)
     cfg = main_wl.cfg
@@ -197,7 +221,8 @@ def main():
                                f"{'M1' if cfg.mode == 1 else 'M2'} rank={cfg.rank}",
                    "accum": args.accum, "step": "quantize_act_fp8 + w4a8_gemm" + ("_lorc" if cfg.rank else "")},
         "roofline": {"bound": "mfma", "achieved": round(gemm_tflops, 3), "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4), "traffic": None,
+                     "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
+                     "traffic": measured_traffic(f"{args.workload} M={args.M} {args.accum}"),
                      "kernel": "k_gemm_tile", "kernel_ms": round(gemm_ms, 5)},
     }
     del main_wl
