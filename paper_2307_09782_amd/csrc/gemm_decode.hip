@@ -1,0 +1,218 @@
+// W4A8 GEMM for at most 16 tokens (decode): a persistent weight-streaming
+// kernel, bound by reading the packed FP4 weights once from HBM.
+//
+//   Y[m,n] = (sx[m] c[n]) * sum_k a[m,k] * q[k,n] * 2^e[g(k),n]   (+ T.V, LoRC)
+//
+// (paper Sections 1 and 3.)  One workgroup of NW = 8 or 16 waves per compute unit
+// walks over strips of 16 output channels.  Wave w owns the k-tiles w, w+NW, ... of
+// every strip, so its activation fragments (the A operands of
+// v_mfma_scale_f32_16x16x128_f8f6f4) are loaded ONCE and stay in registers for the whole
+// kernel; the only traffic in the loop is the weight stream: one contiguous
+// 1 KB fragment per matrix instruction plus its exponent dword.  The fragments
+// of the next strip are in flight while the current strip is multiplied,
+// reduced across the waves in LDS (fixed order, no atomics) and stored.
+#include "zqfp_internal.h"
+
+namespace zqfp {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+
+__device__ inline uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
+    return (uint16_t)(u >> 16);
+}
+
+// NW: waves per workgroup (8 or 16); KPW: k-tiles per wave (K / 128 / NW, rounded up); NB: fragment
+// buffers, i.e. NB - 1 strips in flight behind the one being multiplied.  One workgroup per compute
+// unit: NW / 4 waves per SIMD.
+template <int NW, int KPW, int NB, bool EXACT>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void k_gemm_decode(
+    const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int M, const uint8_t* __restrict__ blob, BlobLayout L,
+    Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype)
+{
+    constexpr int kWaves = NW;
+    __shared__ float s_red[2][kWaves][64][4];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 15, lb = lane >> 4;
+    const int nkt = (int)L.nkt;
+    const int64_t nstrips = L.nstrips;
+
+    // ---- activation fragments: lane (row = lane%16, lb) holds bytes k = 16*lb + [0,16) and
+    // k = 64 + 16*lb + [0,16) of each of its k-tiles; rows past M are zero
+    v8i afr[KPW];
+#pragma unroll
+    for (int u = 0; u < KPW; ++u) {
+        const int kt = wave + kWaves * u;
+        v8i a = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (kt < nkt && col < M) {
+            const uint8_t* p = Xq + (int64_t)col * L.K + (int64_t)kt * 128 + 16 * lb;
+            const u32x4 x0 = *reinterpret_cast<const u32x4*>(p);
+            const u32x4 x1 = *reinterpret_cast<const u32x4*>(p + 64);
+            a = (v8i){(int)x0[0], (int)x0[1], (int)x0[2], (int)x0[3], (int)x1[0], (int)x1[1], (int)x1[2], (int)x1[3]};
+        }
+        afr[u] = a;
+    }
+    // stored exponent group of this lane's 32-block of its u-th k-tile (recomputed where needed:
+    // a few integer operations, cheaper than holding it in registers)
+    const bool small_groups = L.gsb < 4;  // groups of 32 or 64: a shift; else one group per k-tile
+    auto stored_group = [&](int u) {
+        const int kt = min(wave + kWaves * u, nkt - 1);
+        const int a = (kt * 4 + lb) >> (small_groups ? L.gsb_shift : 0);
+        const int b = (int)(((uint32_t)kt * L.gq_magic) >> 16);  // kt / (gsb / 4), exact for kt <= 64
+        return small_groups ? a : b;
+    };
+
+    const u32x4* bfrag = reinterpret_cast<const u32x4*>(blob + L.off_codes) + lane;
+    const uint32_t* exq = reinterpret_cast<const uint32_t*>(blob + L.off_exps);
+    const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
+
+    u32x4 b[NB][KPW];
+    uint32_t e[NB][KPW];
+
+    // ---- epilogue operands.  Thread t < 256 owns output (row t / 16, column t % 16) of every
+    // strip: its token scale and LoRC row are loaded once; the column scale and the LoRC column
+    // of a strip travel with that strip's fragments, so that no load sits on the path between
+    // the reduction and the store.
+    constexpr int RMAX = 8;  // LoRC ranks up to 8 are held in registers, larger ones are read in place
+    const bool ep_thread = tid < 256;
+    const int er = tid >> 4, ec = tid & 15;
+    const bool row_live = ep_thread && er < M;
+    const int rk = lorc.r;
+    float sx_r = 0.f, t_r[RMAX];
+#pragma unroll
+    for (int j = 0; j < RMAX; ++j) t_r[j] = 0.f;
+    if (row_live) {
+        sx_r = sx[er];
+        if (rk <= RMAX)
+            for (int j = 0; j < RMAX; ++j)
+                if (j < rk) t_r[j] = lorc.T[er * rk + j];
+    }
+    float cs[NB], vv[NB][RMAX];
+
+    auto issue = [&](int buf, int64_t strip) {
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+            const int kt = min(wave + kWaves * u, nkt - 1);  // clamped duplicates are multiplied by zero fragments
+            b[buf][u] = bfrag[(strip * nkt + kt) * 64];
+            e[buf][u] = exq[strip * L.ngq * 16 + (stored_group(u) >> 2) * 16 + col];
+        }
+        if (ep_thread) {
+            const int64_t n = min(strip * 16 + ec, L.N - 1);
+            cs[buf] = colscale[n];
+#pragma unroll
+            for (int j = 0; j < RMAX; ++j) vv[buf][j] = (j < rk && rk <= RMAX) ? half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]) : 0.f;
+        }
+    };
+    auto finish = [&](int buf, int64_t strip, int par) {
+        v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // two chains: half the dependent latency
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+            const v8i bv = {(int)b[buf][u][0], (int)b[buf][u][1], (int)b[buf][u][2], (int)b[buf][u][3], 0, 0, 0, 0};
+            const int sc = (int)(e[buf][u] >> (8 * (stored_group(u) & 3)));
+            v4f& acc = (u & 1) ? acc1 : acc0;
+            // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
+            if constexpr (EXACT) {
+                // the split costs 40 VALU operations per fragment: free next to a 1 KB HBM read.  The
+                // empty asm keeps the compiler from hoisting the (loop-invariant) halves into registers.
+                v8i a = afr[u], hi, lo;
+                asm volatile("" : "+v"(a));
+                split_exponent_bands(a, hi, lo);
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc, 0, 4, 0, 127, 0, sc);
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lo, bv, acc, 0, 4, 0, 127, 0, sc);
+                __builtin_amdgcn_sched_barrier(0);  // one pair of halves alive at a time
+            } else {
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, acc, 0, 4, 0, 127, 0, sc);
+            }
+        }
+        *reinterpret_cast<v4f*>(&s_red[par][wave][lane][0]) = acc0 + acc1;
+        __syncthreads();
+        // D[row][col] sits in lane 16*(row/4)+col, register row%4
+        const int64_t n = strip * 16 + ec;
+        if (row_live && n < L.N) {
+            const int src = 16 * (er >> 2) + ec, reg = er & 3;
+            float a = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) a += s_red[par][w][src][reg];
+            float y = (sx_r * cs[buf]) * a;
+            if (rk <= RMAX) {
+#pragma unroll
+                for (int j = 0; j < RMAX; ++j)
+                    if (j < rk) y = fmaf(t_r[j], vv[buf][j], y);
+            } else {
+                for (int j = 0; j < rk; ++j)
+                    y = fmaf(lorc.T[er * rk + j], half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]), y);
+            }
+            if (out_dtype == 0) reinterpret_cast<float*>(Y)[er * ldy + n] = y;
+            else reinterpret_cast<uint16_t*>(Y)[er * ldy + n] = f32_to_bf16_bits(y);
+        }
+    };
+
+    // ---- strips blockIdx.x, + gridDim.x, ...; NB - 1 strips are in flight behind the current one.
+    // The loop is unrolled by NB so that the fragment buffers are addressed statically.  The LDS
+    // reduction buffer alternates per strip: it is rewritten two strips later, after a barrier
+    // that every reader has passed.
+    const int64_t stride = gridDim.x;
+    int64_t s = blockIdx.x;
+#pragma unroll
+    for (int r = 0; r < NB - 1; ++r)
+        if (s + r * stride < nstrips) issue(r, s + r * stride);
+    int par = 0;
+    while (s < nstrips) {
+#pragma unroll
+        for (int r = 0; r < NB; ++r) {
+            if (s < nstrips) {
+                const int64_t ahead = s + (NB - 1) * stride;
+                if (ahead < nstrips) issue((r + NB - 1) % NB, ahead);
+                finish(r, s, par);
+                par ^= 1;
+            }
+            s += stride;
+        }
+    }
+}
+
+template <int NW, int KPW, int NB>
+void launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
+                const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+{
+    if (exact)
+        hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, true>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
+    else
+        hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, false>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
+}
+
+}  // namespace
+
+bool gemm_decode_supported(int64_t M, const BlobLayout& L) { return M >= 1 && M <= 16 && L.nkt <= 64; }
+
+hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                              Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
+{
+    if (L.N == 0) return hipSuccess;
+    static int cus = 0;  // compute units of the (single) device, asked once
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);  // one persistent workgroup per compute unit
+    const bool exact = accum == 0;
+    const int m = (int)M;
+    const int nkt = (int)L.nkt;
+    if (nkt <= 8) launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    else if (nkt <= 16) launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    else if (nkt <= 32) launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    else if (nkt <= 40) launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    else launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    return hipGetLastError();
+}
+
+}  // namespace zqfp

@@ -34,7 +34,9 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
     zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* blob = static_cast<const uint8_t*>(packed);
-    hipError_t e = zqfp::gemm_tile_supported(M, L)
+    hipError_t e = zqfp::gemm_decode_supported(M, L)
+                       ? zqfp::launch_gemm_decode(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                   : zqfp::gemm_tile_supported(M, L)
                        ? zqfp::launch_gemm_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
                        : zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);

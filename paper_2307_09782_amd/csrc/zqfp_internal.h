@@ -45,6 +45,7 @@ struct BlobLayout {
     int G, Gs, ngs, ngq;
     int gsb;        // 32-element blocks per stored group (Gs / 32)
     int gsb_shift;  // log2(gsb) if gsb is a power of two, else -1
+    uint32_t gq_magic;  // groups of >= 128: stored group of k-tile kt is (kt * gq_magic) >> 16 for kt <= 64
     size_t off_codes, off_exps, off_colscale, total;
 };
 
@@ -62,6 +63,10 @@ inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
     L->gsb = L->Gs / 32;
     L->gsb_shift = -1;
     for (int s = 0; s < 16; ++s) if ((1 << s) == L->gsb) L->gsb_shift = s;
+    {
+        const int gq = L->gsb >= 4 ? L->gsb / 4 : 1;  // k-tiles per stored group
+        L->gq_magic = (uint32_t)((65536 + gq - 1) / gq);
+    }
     L->off_codes = 256;
     L->off_exps = L->off_codes + (size_t)L->Np * (size_t)K / 2;
     size_t exps_bytes = (size_t)L->nstrips * L->ngq * 64;
@@ -110,5 +115,9 @@ hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const
                             const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                             int accum, hipStream_t s);
 bool gemm_tile_supported(int64_t M, const BlobLayout& L);
+hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
+                              const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
+                              int accum, hipStream_t s);
+bool gemm_decode_supported(int64_t M, const BlobLayout& L);
 
 }  // namespace zqfp
