@@ -31,14 +31,15 @@ __device__ inline uint16_t f32_to_bf16_bits(float f)
 // NW: waves per workgroup (8 or 16); KPW: k-tiles per wave (K / 128 / NW, rounded up); NB: fragment
 // buffers, i.e. NB - 1 strips in flight behind the one being multiplied.  One workgroup per compute
 // unit: NW / 4 waves per SIMD.
-template <int NW, int KPW, int NB, bool EXACT>
+template <int NW, int KPW, int NB, bool EXACT, bool LR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void k_gemm_decode(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int M, const uint8_t* __restrict__ blob, BlobLayout L,
     Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype)
 {
     constexpr int kWaves = NW;
     __shared__ float s_red[2][kWaves][64][4];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: fragment addresses stay in SGPRs
     const int col = lane & 15, lb = lane >> 4;
     const int nkt = (int)L.nkt;
     const int64_t nstrips = L.nstrips;
@@ -68,45 +69,53 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         return small_groups ? a : b;
     };
 
-    const u32x4* bfrag = reinterpret_cast<const u32x4*>(blob + L.off_codes) + lane;
+    const uint8_t* codes = blob + L.off_codes;
     const uint32_t* exq = reinterpret_cast<const uint32_t*>(blob + L.off_exps);
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
 
     u32x4 b[NB][KPW];
     uint32_t e[NB][KPW];
 
-    // ---- epilogue operands.  Thread t < 256 owns output (row t / 16, column t % 16) of every
+    // ---- epilogue operands.  Thread t (mod 256) owns output (row t / 16, column t % 16) of every
     // strip: its token scale and LoRC row are loaded once; the column scale and the LoRC column
     // of a strip travel with that strip's fragments, so that no load sits on the path between
-    // the reduction and the store.
+    // the reduction and the store.  Every load of the loop is unconditional (addresses are clamped
+    // into valid memory instead) and its value is left raw until it is used: the load counter can
+    // then be waited on exactly, and a strip's operands never wait for the next strip's.
     constexpr int RMAX = 8;  // LoRC ranks up to 8 are held in registers, larger ones are read in place
-    const bool ep_thread = tid < 256;
-    const int er = tid >> 4, ec = tid & 15;
-    const bool row_live = ep_thread && er < M;
+    const int er = (tid >> 4) & 15, ec = tid & 15;
+    const bool row_live = tid < 256 && er < M;
     const int rk = lorc.r;
+    constexpr bool lorc_regs = LR;  // 0 < rk <= RMAX (the launcher's choice)
     float sx_r = 0.f, t_r[RMAX];
 #pragma unroll
     for (int j = 0; j < RMAX; ++j) t_r[j] = 0.f;
     if (row_live) {
         sx_r = sx[er];
-        if (rk <= RMAX)
+        if (lorc_regs)
             for (int j = 0; j < RMAX; ++j)
                 if (j < rk) t_r[j] = lorc.T[er * rk + j];
     }
-    float cs[NB], vv[NB][RMAX];
+    float cs[NB];
+    uint32_t vv[NB][RMAX];  // binary16 bits
+#pragma unroll
+    for (int r = 0; r < NB; ++r)
+#pragma unroll
+        for (int j = 0; j < RMAX; ++j) vv[r][j] = 0u;
 
-    auto issue = [&](int buf, int64_t strip) {
+    auto issue = [&](int buf, int64_t strip_unclamped) {
+        const int64_t strip = min(strip_unclamped, nstrips - 1);  // past the end: the last strip again, never used
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
             const int kt = min(wave + kWaves * u, nkt - 1);  // clamped duplicates are multiplied by zero fragments
-            b[buf][u] = bfrag[(strip * nkt + kt) * 64];
-            e[buf][u] = exq[strip * L.ngq * 16 + (stored_group(u) >> 2) * 16 + col];
+            b[buf][u] = reinterpret_cast<const u32x4*>(codes + ((strip * nkt + kt) << 10))[lane];
+            e[buf][u] = (exq + strip * L.ngq * 16)[(stored_group(u) >> 2) * 16 + col];
         }
-        if (ep_thread) {
-            const int64_t n = min(strip * 16 + ec, L.N - 1);
-            cs[buf] = colscale[n];
+        const int64_t n = min(strip * 16 + ec, L.N - 1);
+        cs[buf] = colscale[n];
+        if constexpr (LR) {
 #pragma unroll
-            for (int j = 0; j < RMAX; ++j) vv[buf][j] = (j < rk && rk <= RMAX) ? half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]) : 0.f;
+            for (int j = 0; j < RMAX; ++j) vv[buf][j] = lorc.V[(int64_t)min(j, rk - 1) * L.N + n];
         }
     };
     auto finish = [&](int buf, int64_t strip, int par) {
@@ -132,22 +141,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         }
         *reinterpret_cast<v4f*>(&s_red[par][wave][lane][0]) = acc0 + acc1;
         __syncthreads();
-        // D[row][col] sits in lane 16*(row/4)+col, register row%4
+        // D[row][col] sits in lane 16*(row/4)+col, register row%4.  Every thread sums (the upper
+        // half of the workgroup repeats the lower half's work): only the store is predicated, so
+        // the loop body stays one basic block and the load counters stay exact.
         const int64_t n = strip * 16 + ec;
+        const int src = 16 * (er >> 2) + ec, reg = er & 3;
+        float a = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) a += s_red[par][w][src][reg];
+        float y = (sx_r * cs[buf]) * a;
+        if constexpr (LR) {
+#pragma unroll
+            for (int j = 0; j < RMAX; ++j) y = fmaf(t_r[j], j < rk ? half_bits_to_f32((uint16_t)vv[buf][j]) : 0.f, y);
+        }
         if (row_live && n < L.N) {
-            const int src = 16 * (er >> 2) + ec, reg = er & 3;
-            float a = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) a += s_red[par][w][src][reg];
-            float y = (sx_r * cs[buf]) * a;
-            if (rk <= RMAX) {
-#pragma unroll
-                for (int j = 0; j < RMAX; ++j)
-                    if (j < rk) y = fmaf(t_r[j], vv[buf][j], y);
-            } else {
+            if (rk > RMAX)
                 for (int j = 0; j < rk; ++j)
                     y = fmaf(lorc.T[er * rk + j], half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]), y);
-            }
             if (out_dtype == 0) reinterpret_cast<float*>(Y)[er * ldy + n] = y;
             else reinterpret_cast<uint16_t*>(Y)[er * ldy + n] = f32_to_bf16_bits(y);
         }
@@ -160,19 +170,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int64_t stride = gridDim.x;
     int64_t s = blockIdx.x;
 #pragma unroll
-    for (int r = 0; r < NB - 1; ++r)
-        if (s + r * stride < nstrips) issue(r, s + r * stride);
+    for (int r = 0; r < NB - 1; ++r) issue(r, s + r * stride);
     int par = 0;
-    while (s < nstrips) {
+    while (true) {
 #pragma unroll
         for (int r = 0; r < NB; ++r) {
-            if (s < nstrips) {
-                const int64_t ahead = s + (NB - 1) * stride;
-                if (ahead < nstrips) issue((r + NB - 1) % NB, ahead);
-                finish(r, s, par);
-                par ^= 1;
-            }
+            issue((r + NB - 1) % NB, s + (NB - 1) * stride);
+            __builtin_amdgcn_sched_barrier(0);
+            finish(r, s, par);
+            __builtin_amdgcn_sched_barrier(0);
+            par ^= 1;
             s += stride;
+            if (s >= nstrips) return;
         }
     }
 }
@@ -181,15 +190,17 @@ template <int NW, int KPW, int NB>
 void launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
                 const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
-    if (exact)
-        hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, true>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
-    else
-        hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, false>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
+    const bool lr = lorc.r > 0 && lorc.r <= 8;  // LoRC operands held in registers
+#define ZQ_LAUNCH(EX, LR) \
+    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype)
+    if (exact) { if (lr) ZQ_LAUNCH(true, true); else ZQ_LAUNCH(true, false); }
+    else       { if (lr) ZQ_LAUNCH(false, true); else ZQ_LAUNCH(false, false); }
+#undef ZQ_LAUNCH
 }
 
 }  // namespace
 
-bool gemm_decode_supported(int64_t M, const BlobLayout& L) { return M >= 1 && M <= 16 && L.nkt <= 64; }
+bool gemm_decode_supported(int64_t M, const BlobLayout& L) { return M >= 1 && M <= 16 && L.nkt <= 64; }  // gq_magic is exact up to 64 k-tiles
 
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
                               Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
@@ -203,10 +214,10 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
             n = 256;
         cus = n;
     }
-    const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);  // one persistent workgroup per compute unit
     const bool exact = accum == 0;
     const int m = (int)M;
     const int nkt = (int)L.nkt;
+    const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);  // one persistent workgroup per compute unit
     if (nkt <= 8) launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
     else if (nkt <= 16) launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
     else if (nkt <= 32) launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
