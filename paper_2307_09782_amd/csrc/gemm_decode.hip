@@ -37,7 +37,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype)
 {
     constexpr int kWaves = NW;
+    constexpr bool HI_LDS = EXACT && KPW >= 8;
     __shared__ float s_red[2][kWaves][64][4];
+    extern __shared__ __attribute__((aligned(16))) uint8_t s_hi[];  // HI_LDS: NW * KPW * 2048 bytes
+
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: fragment addresses stay in SGPRs
     const int col = lane & 15, lb = lane >> 4;
@@ -45,19 +48,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int64_t nstrips = L.nstrips;
 
     // ---- activation fragments: lane (row = lane%16, lb) holds bytes k = 16*lb + [0,16) and
-    // k = 64 + 16*lb + [0,16) of each of its k-tiles; rows past M are zero
+    // k = 64 + 16*lb + [0,16) of each of its k-tiles.  The loads are unconditional: a row past M
+    // repeats row M - 1 (row m of the product depends on row m of A only, and rows past M are
+    // never stored), a k-tile past the end repeats the last one and is zeroed further down, once
+    // the first strips' weight loads have been issued behind these.
+    u32x4 ax0[KPW], ax1[KPW];
+    // The fragments are filled from ax0/ax1 below.  In the exact mode they are split into their two
+    // exponent bands once (they serve every strip): afr holds the lower band, ahi the upper one,
+    // or, when 8 k-tiles per wave leave no registers for it, the wave's own slice of LDS does.
     v8i afr[KPW];
+    v8i ahi[(EXACT && !HI_LDS) ? KPW : 1];
 #pragma unroll
     for (int u = 0; u < KPW; ++u) {
-        const int kt = wave + kWaves * u;
-        v8i a = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (kt < nkt && col < M) {
-            const uint8_t* p = Xq + (int64_t)col * L.K + (int64_t)kt * 128 + 16 * lb;
-            const u32x4 x0 = *reinterpret_cast<const u32x4*>(p);
-            const u32x4 x1 = *reinterpret_cast<const u32x4*>(p + 64);
-            a = (v8i){(int)x0[0], (int)x0[1], (int)x0[2], (int)x0[3], (int)x1[0], (int)x1[1], (int)x1[2], (int)x1[3]};
-        }
-        afr[u] = a;
+        const int kt = min(wave + kWaves * u, nkt - 1);
+        const uint8_t* p = Xq + (int64_t)min(col, M - 1) * L.K + (int64_t)kt * 128 + 16 * lb;
+        ax0[u] = *reinterpret_cast<const u32x4*>(p);
+        ax1[u] = *reinterpret_cast<const u32x4*>(p + 64);
     }
     // stored exponent group of this lane's 32-block of its u-th k-tile (recomputed where needed:
     // a few integer operations, cheaper than holding it in registers)
@@ -86,15 +92,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int er = (tid >> 4) & 15, ec = tid & 15;
     const bool row_live = tid < 256 && er < M;
     const int rk = lorc.r;
-    constexpr bool lorc_regs = LR;  // 0 < rk <= RMAX (the launcher's choice)
-    float sx_r = 0.f, t_r[RMAX];
+    float sx_r = sx[min(er, M - 1)], t_r[RMAX];
 #pragma unroll
     for (int j = 0; j < RMAX; ++j) t_r[j] = 0.f;
-    if (row_live) {
-        sx_r = sx[er];
-        if (lorc_regs)
-            for (int j = 0; j < RMAX; ++j)
-                if (j < rk) t_r[j] = lorc.T[er * rk + j];
+    if constexpr (LR) {
+#pragma unroll
+        for (int j = 0; j < RMAX; ++j) t_r[j] = lorc.T[min(er, M - 1) * rk + min(j, rk - 1)];  // j >= rk: unused
     }
     float cs[NB];
     uint32_t vv[NB][RMAX];  // binary16 bits
@@ -119,7 +122,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         }
     };
     auto finish = [&](int buf, int64_t strip, int par) {
-        v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // two chains: half the dependent latency
+        // independent accumulator chains (two; four in the exact mode, one pair per exponent band):
+        // a matrix instruction that waits for the previous one's result costs its full latency
+        v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
             const v8i bv = {(int)b[buf][u][0], (int)b[buf][u][1], (int)b[buf][u][2], (int)b[buf][u][3], 0, 0, 0, 0};
@@ -127,19 +132,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
             v4f& acc = (u & 1) ? acc1 : acc0;
             // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
             if constexpr (EXACT) {
-                // the split costs 40 VALU operations per fragment: free next to a 1 KB HBM read.  The
-                // empty asm keeps the compiler from hoisting the (loop-invariant) halves into registers.
-                v8i a = afr[u], hi, lo;
-                asm volatile("" : "+v"(a));
-                split_exponent_bands(a, hi, lo);
+                v4f& accl = (u & 1) ? acc3 : acc2;
+                v8i hi;
+                if constexpr (HI_LDS) {
+                    const u32x4 h0 = *reinterpret_cast<const u32x4*>(s_hi + ((wave * KPW + u) * 128 + lane) * 16);
+                    const u32x4 h1 = *reinterpret_cast<const u32x4*>(s_hi + ((wave * KPW + u) * 128 + 64 + lane) * 16);
+                    hi = (v8i){(int)h0[0], (int)h0[1], (int)h0[2], (int)h0[3], (int)h1[0], (int)h1[1], (int)h1[2], (int)h1[3]};
+                } else {
+                    hi = ahi[u];
+                }
                 acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc, 0, 4, 0, 127, 0, sc);
-                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lo, bv, acc, 0, 4, 0, 127, 0, sc);
-                __builtin_amdgcn_sched_barrier(0);  // one pair of halves alive at a time
+                accl = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, accl, 0, 4, 0, 127, 0, sc);
             } else {
                 acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, acc, 0, 4, 0, 127, 0, sc);
             }
         }
-        *reinterpret_cast<v4f*>(&s_red[par][wave][lane][0]) = acc0 + acc1;
+        *reinterpret_cast<v4f*>(&s_red[par][wave][lane][0]) = EXACT ? (acc0 + acc1) + (acc2 + acc3) : acc0 + acc1;
         __syncthreads();
         // D[row][col] sits in lane 16*(row/4)+col, register row%4.  Every thread sums (the upper
         // half of the workgroup repeats the lower half's work): only the store is predicated, so
@@ -155,7 +163,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
             for (int j = 0; j < RMAX; ++j) y = fmaf(t_r[j], j < rk ? half_bits_to_f32((uint16_t)vv[buf][j]) : 0.f, y);
         }
         if (row_live && n < L.N) {
-            if (rk > RMAX)
+            if (!LR && rk > 0)  // ranks not held in registers: read in place
                 for (int j = 0; j < rk; ++j)
                     y = fmaf(lorc.T[er * rk + j], half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]), y);
             if (out_dtype == 0) reinterpret_cast<float*>(Y)[er * ldy + n] = y;
@@ -171,6 +179,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     int64_t s = blockIdx.x;
 #pragma unroll
     for (int r = 0; r < NB - 1; ++r) issue(r, s + r * stride);
+#pragma unroll
+    for (int u = 0; u < KPW; ++u) {
+        const bool live = wave + kWaves * u < nkt;  // uniform
+        const u32x4 x0 = live ? ax0[u] : (u32x4){0u, 0u, 0u, 0u}, x1 = live ? ax1[u] : (u32x4){0u, 0u, 0u, 0u};
+        const v8i a = {(int)x0[0], (int)x0[1], (int)x0[2], (int)x0[3], (int)x1[0], (int)x1[1], (int)x1[2], (int)x1[3]};
+        if constexpr (EXACT) {
+            v8i hi;
+            split_exponent_bands(a, hi, afr[u]);
+            if constexpr (HI_LDS) {
+                *reinterpret_cast<u32x4*>(s_hi + ((wave * KPW + u) * 128 + lane) * 16) = (u32x4){(uint32_t)hi[0], (uint32_t)hi[1], (uint32_t)hi[2], (uint32_t)hi[3]};
+                *reinterpret_cast<u32x4*>(s_hi + ((wave * KPW + u) * 128 + 64 + lane) * 16) = (u32x4){(uint32_t)hi[4], (uint32_t)hi[5], (uint32_t)hi[6], (uint32_t)hi[7]};
+            } else {
+                ahi[u] = hi;
+            }
+        } else {
+            afr[u] = a;
+        }
+    }
     int par = 0;
     while (true) {
 #pragma unroll
@@ -187,15 +213,32 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 }
 
 template <int NW, int KPW, int NB>
-void launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
+hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
                 const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
-    const bool lr = lorc.r > 0 && lorc.r <= 8;  // LoRC operands held in registers
+    // LoRC operands of ranks up to 8 are held in registers
+    const bool lr = lorc.r > 0 && lorc.r <= 8;
+    // the exact mode with 8 k-tiles per wave keeps the upper-band fragments in LDS (above the 64 KB
+    // default limit of dynamic LDS, which is a per-function setting)
+    const size_t smem = (exact && KPW >= 8) ? (size_t)NW * KPW * 2048 : 0;
+    if (smem > 0) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
 #define ZQ_LAUNCH(EX, LR) \
-    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype)
+    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype)
     if (exact) { if (lr) ZQ_LAUNCH(true, true); else ZQ_LAUNCH(true, false); }
     else       { if (lr) ZQ_LAUNCH(false, true); else ZQ_LAUNCH(false, false); }
 #undef ZQ_LAUNCH
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -218,12 +261,11 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
     const int m = (int)M;
     const int nkt = (int)L.nkt;
     const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);  // one persistent workgroup per compute unit
-    if (nkt <= 8) launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    else if (nkt <= 16) launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    else if (nkt <= 32) launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    else if (nkt <= 40) launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    else launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    return hipGetLastError();
+    if (nkt <= 8) return launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    if (nkt <= 16) return launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    if (nkt <= 32) return launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    if (nkt <= 40) return launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    return launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
 }
 
 }  // namespace zqfp

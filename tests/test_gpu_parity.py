@@ -191,6 +191,9 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (77, 512, 200, 128, 2, 8),      # tiled form, ragged M and N
     (200, 1280, 400, 256, 2, 0),    # tiled form, several tiles each way
     (129, 384, 130, 32, 1, 16),
+    (7, 512, 48, 128, 2, 16),       # decode form, rank too large for registers: read in place
+    (16, 8192, 80, 128, 1, 8),      # decode form, 64 k-tiles (8 per wave) with LoRC
+    (3, 5120, 96, 128, 2, 5),       # decode form, 40 k-tiles (5 per wave)
 ])
 def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
