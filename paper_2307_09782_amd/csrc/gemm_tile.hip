@@ -11,12 +11,17 @@
 // done by the matrix core, no unpack and no multiply).
 //
 // Two waves share a SIMD so that one wave's LDS reads and barrier waits hide
-// behind the other's matrix instructions.  LDS holds two stages; the next
-// stage travels global -> registers during the current step's matrix work and
-// registers -> LDS at its end.  A stage keeps the activation tile in "fragment
-// order" (per 16-row sub-tile: 2 halves x 64 lanes x 16 B, lane = 16*(k/16 % 4)
-// + row) so that every operand read is a conflict-free 16 B/lane read; the
-// weight tile already has that order in memory and is copied as is.
+// behind the other's matrix instructions.  LDS holds three stages.  A stage
+// is filled by LDS-direct loads (global_load_lds_dwordx4: every lane names a
+// 16 B chunk in global memory, the wave's 64 chunks land in one contiguous
+// 1 KB block of LDS), two k-steps ahead of its use: no staging registers, no
+// LDS store instructions, and a full k-step of slack for the memory latency.
+// A stage keeps the activation tile in "fragment order" (per 16-row sub-tile:
+// 2 halves x 64 lanes x 16 B, lane = 16*(k/16 % 4) + row) so that every operand
+// read is a conflict-free 16 B/lane read; the weight tile already has that
+// order in memory and is copied as is.
+#include <type_traits>
+
 #include "zqfp_internal.h"
 
 namespace zqfp {
@@ -33,6 +38,26 @@ __device__ inline uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+// LDS-direct loads.  Lane l of the wave fetches 16 (or 4) bytes at gbase + voff and the hardware
+// writes them to LDS byte address lds_base + 16 (4) * l; lds_base travels in M0 and is uniform.
+// The compiler knows nothing of these loads or of their LDS writes: they are waited for by hand
+// (wait_loads_then_barrier) and M0 has no other user in this file.
+__device__ inline void lds_load16(const uint8_t* gbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ inline void lds_load4(const uint8_t* gbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+// Waits until at most N of this wave's loads are outstanding (loads complete in order) and for
+// its LDS traffic, then joins the workgroup barrier.
+template <int N>
+__device__ inline void wait_loads_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
 template <int WTM, int WTN, int WAVES_M, int WAVES_N>
 struct TileCfg {
     static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
@@ -40,6 +65,7 @@ struct TileCfg {
     static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 64;
     static constexpr int E_BYTES = THREADS * 4;               // one exponent dword per output channel (first BN used)
     static constexpr int STAGE = A_BYTES + B_BYTES + E_BYTES;
+    static constexpr int NSTAGE = 3;
     static constexpr int A_CHUNKS = A_BYTES / 16 / THREADS;  // 16 B chunks per thread
     static constexpr int B_CHUNKS = B_BYTES / 16 / THREADS;
     static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile / thread mismatch");
@@ -77,22 +103,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     const int tm = first_m + (pid % in_group) % gsz;
     const int tn = (pid % in_group) / gsz;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS block addresses go to M0
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int col = lane & 15, lb = lane >> 4;
     const int64_t m0 = (int64_t)tm * C::BM;
     const int64_t strip0 = (int64_t)tn * (C::BN / 16);
     const int nkt = (int)L.nkt;
 
-    // ---- staging addresses: uniform base pointers plus small per-thread offsets.  Rows past M
+    // ---- load addresses: uniform base pointers plus 32-bit per-lane offsets.  Rows past M
     // and strips past the last one are clamped to the last valid one: what they produce is
-    // never stored.
+    // never stored.  Chunk (wave, i) of the activation tile is the 1 KB block (sub-tile
+    // wave/2 + (THREADS/128)*i, half wave%2): lane l fetches row l%16, bytes 16*(l/16 + 4*half)
+    // + [0,16) of the k-tile.  Chunk (wave, i) of the weight tile is strip wave + (THREADS/64)*i,
+    // 1 KB contiguous in memory.
     const uint8_t* a_base = Xq + m0 * L.K;                    // uniform
     const uint8_t* b_base = blob + L.off_codes;               // uniform
-    const uint32_t* e_base = reinterpret_cast<const uint32_t*>(blob + L.off_exps);
+    const uint8_t* e_base = blob + L.off_exps;                // uniform
     const int rows_here = (int)min((int64_t)C::BM, M - m0);   // >= 1
     uint32_t a_off[C::A_CHUNKS], b_off[C::B_CHUNKS];
-    const int a_dst0 = (tid >> 7) * 2048 + ((tid >> 6) & 1) * 1024 + (((tid >> 4) & 3) * 16 + (tid & 15)) * 16;
 #pragma unroll
     for (int i = 0; i < C::A_CHUNKS; ++i) {
         const int cidx = tid + kThreads * i;
@@ -105,10 +134,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         const int64_t strip = min(strip0 + (cidx >> 6), L.nstrips - 1);
         b_off[i] = (uint32_t)((strip * nkt * 64 + (cidx & 63)) * 16);
     }
-    // exponent dwords, [strip][quad][column] in memory: thread t < BN stages the dword of
-    // column t of the tile; it lands in LDS as [column] and every lane later picks its own.
-    // (Threads past BN stage a duplicate into padding: the loop body stays free of branches.)
-    const uint32_t e_off = (uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15);
+    // exponent dwords, [strip][quad][column] in memory: thread t stages the dword of column
+    // t % BN of the tile; it lands in LDS as [column] and every lane later picks its own.
+    const uint32_t e_off = 4u * ((uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15));
+    // LDS byte addresses (the dynamic array is the kernel's only LDS object)
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
+    const uint32_t a_dst = lds0 + ((wave >> 1) * 2048 + (wave & 1) * 1024);
+    const uint32_t b_dst = lds0 + C::A_BYTES + wave * 1024;
+    const uint32_t e_dst = lds0 + C::A_BYTES + C::B_BYTES + wave * 256;
 
     // stored exponent group of a 32-block.  Stored groups are 32 or 64 wide (then a shift of the
     // block index does it) or a multiple of 128 (then all four blocks of k-tile kt share group
@@ -120,32 +153,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     auto group_of = [&](const GroupCursor& c, int kt, int b) {
         return small_groups ? ((kt * 4 + b) >> L.gsb_shift) : c.g;
     };
-    auto advance = [&](GroupCursor& c, bool moved) {
-        const int sub = c.sub + (moved ? 1 : 0);
+    auto advance = [&](GroupCursor& c) {
+        const int sub = c.sub + 1;
         const bool wrap = sub == gq;
         c.sub = wrap ? 0 : sub;
         c.g += wrap ? 1 : 0;
     };
 
-    // ---- register staging of one stage: A_CHUNKS + B_CHUNKS 16-byte chunks and one exponent dword
-    u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
-    uint32_t re = 0;
+    // ---- one stage = NSIDE loads per wave: A_CHUNKS + B_CHUNKS 1 KB blocks and 256 B of exponents
     constexpr int NSIDE = C::A_CHUNKS + C::B_CHUNKS + 1;
-    // t-th global load of k-tile kt into the staging registers
-    auto side_load = [&](int t, int kt, const GroupCursor& c) {
-        if (t < C::A_CHUNKS) ra[t] = *reinterpret_cast<const u32x4*>(a_base + a_off[t] + kt * 128);
+    // t-th load of k-tile kt into LDS stage `stage`
+    auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) {
+        const uint32_t st = (uint32_t)stage * C::STAGE;
+        if (t < C::A_CHUNKS) lds_load16(a_base + kt * 128, a_off[t], st + a_dst + t * (kThreads / 128) * 2048);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            rb[t - C::A_CHUNKS] = *reinterpret_cast<const u32x4*>(b_base + b_off[t - C::A_CHUNKS] + kt * 1024);
+            lds_load16(b_base + (int64_t)kt * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kThreads / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
-            re = e_base[e_off + (group_of(c, kt, 0) >> 2) * 16];
-    };
-    // t-th store of the staging registers into LDS stage `stage`
-    auto side_store = [&](int t, int stage) {
-        uint8_t* st = smem + stage * C::STAGE;
-        if (t < C::A_CHUNKS) *reinterpret_cast<u32x4*>(st + a_dst0 + t * (kThreads / 128) * 2048) = ra[t];
-        else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            *reinterpret_cast<u32x4*>(st + C::A_BYTES + tid * 16 + (t - C::A_CHUNKS) * kThreads * 16) = rb[t - C::A_CHUNKS];
-        else *reinterpret_cast<uint32_t*>(st + C::A_BYTES + C::B_BYTES + tid * 4) = re;
+            lds_load4(e_base + (group_of(c, kt, 0) >> 2) * 64, e_off, st + e_dst);
     };
 
     v4f acc[WTM][WTN];
@@ -154,30 +178,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
 #pragma unroll
         for (int j = 0; j < WTN; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // ---- prologue: k-tile 0 into stage 0, k-tile 1 into the staging registers
+    // ---- one k-step: the matrix instructions of k-tile kt on LDS stage `stage`.  In-order issue
+    // means that whatever a wave puts between two matrix instructions runs in the shadow of the
+    // matrix pipe; so, when LOAD is set, the loads of k-tile kt + 2 into the stage that the previous
+    // step has just released are dealt out one per matrix instruction, and the scheduling fences
+    // pin that order.  The body has no branches.
     GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
-#pragma unroll
-    for (int t = 0; t < NSIDE; ++t) side_load(t, 0, cur_load);
-#pragma unroll
-    for (int t = 0; t < NSIDE; ++t) side_store(t, 0);
-    int kt_load = min(1, nkt - 1);
-    advance(cur_load, kt_load != 0);
-#pragma unroll
-    for (int t = 0; t < NSIDE; ++t) side_load(t, kt_load, cur_load);
-    __syncthreads();
-
-    // ---- main loop.  In-order issue means that whatever a wave puts between two matrix
-    // instructions runs in the shadow of the matrix pipe, and whatever it puts after the last one
-    // waits for all of them.  So the stores of the staged k-tile (kt + 1) into the other LDS stage
-    // and the loads of k-tile kt + 2 are dealt out one per matrix instruction, and the scheduling
-    // fences pin that order.  Past the end the loads are clamped to the last k-tile (valid memory,
-    // never used): the loop body has no branches.
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int stage = kt & 1;
-        const int kt_next = min(kt_load + 1, nkt - 1);
-        GroupCursor cur_next = cur_load;
-        advance(cur_next, kt_next != kt_load);
-
+    auto k_step = [&](int kt, int stage, int stage_load, auto load_tag) {
+        constexpr bool LOAD = decltype(load_tag)::value;
         const uint8_t* sa = smem + stage * C::STAGE + (wm * WTM) * 2048 + lane * 16;
         const uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
         // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
@@ -218,18 +226,52 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
                                                                                   (int)e_cur[j]);
                     const int t = (i * PASSES + p) * WTN + j;  // position in the step's matrix-instruction stream
-                    if (t < NSIDE) side_store(t, stage ^ 1);
-                    else if (t < 2 * NSIDE) side_load(t - NSIDE, kt_next, cur_next);
+                    if (LOAD && t < NSIDE) side_load(t, kt + 2, stage_load, cur_load);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
-        static_assert(WTM * WTN >= 2 * NSIDE, "not enough matrix instructions to carry the staging traffic");
-        kt_load = kt_next;
-        cur_load = cur_next;
-        advance(cur_comp, true);
-        __syncthreads();
+        static_assert(WTM * WTN >= NSIDE, "not enough matrix instructions to carry the loads");
+        advance(cur_comp);
+        if (LOAD) advance(cur_load);
+    };
+
+    // ---- prologue: k-tiles 0 and 1 into stages 0 and 1
+#pragma unroll
+    for (int t = 0; t < NSIDE; ++t) side_load(t, 0, 0, cur_load);
+    if (nkt > 1) {
+        advance(cur_load);
+#pragma unroll
+        for (int t = 0; t < NSIDE; ++t) side_load(t, 1, 1, cur_load);
+        advance(cur_load);  // now at k-tile 2
+        wait_loads_then_barrier<NSIDE>();  // k-tile 0 has landed, for every wave
+    } else {
+        wait_loads_then_barrier<0>();
     }
+
+    // ---- main loop.  Step kt computes stage kt % 3 while k-tile kt + 1 is landing in the next stage
+    // and k-tile kt + 2 is being requested into the third, which every wave stopped reading at the
+    // barrier that ended step kt - 1.  Before the barrier that ends step kt each wave waits for all
+    // of its loads but this step's NSIDE: then k-tile kt + 1 is complete once every wave is through.
+    // The last two steps request nothing and are peeled, so the loop body stays free of branches.
+    using with_loads = std::integral_constant<bool, true>;
+    using no_loads = std::integral_constant<bool, false>;
+    int stage = 0, stage_load = 2;
+    auto next = [](int st) { return st == C::NSTAGE - 1 ? 0 : st + 1; };
+    int kt = 0;
+    for (; kt + 2 < nkt; ++kt) {
+        k_step(kt, stage, stage_load, with_loads{});
+        wait_loads_then_barrier<NSIDE>();
+        stage = next(stage);
+        stage_load = next(stage_load);
+    }
+    if (nkt > 1) {
+        k_step(kt, stage, stage_load, no_loads{});
+        wait_loads_then_barrier<0>();
+        stage = next(stage);
+        ++kt;
+    }
+    k_step(kt, stage, stage_load, no_loads{});
 
     // ---- epilogue.  D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4:
     // good for the scale / LoRC arithmetic (one column per lane), bad for stores (64 B runs).
@@ -237,7 +279,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // 16*WTN + 4 floats: the four row groups of a store land on disjoint banks, rows stay 16 B
     // aligned) and writes them out as 16 B per lane, whole rows of the slab at a time.
     constexpr int SLAB_N = 16 * WTN, SLAB_LD = SLAB_N + 4;
-    static_assert(C::THREADS / 64 * 16 * SLAB_LD * 4 <= 2 * C::STAGE, "epilogue patch does not fit the stages");
+    static_assert(C::THREADS / 64 * 16 * SLAB_LD * 4 <= C::NSTAGE * C::STAGE, "epilogue patch does not fit the stages");
     __syncthreads();  // every wave is done reading the stages
     float* patch = reinterpret_cast<float*>(smem) + wave * (16 * SLAB_LD);
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
@@ -308,7 +350,7 @@ hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
     const int ntiles = tiles_m * tiles_n;
     const int per = (ntiles + 7) / 8;
-    const size_t smem = 2 * C::STAGE;
+    const size_t smem = C::NSTAGE * C::STAGE;
     auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, EXACT>;
     static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
     if (!attr_done) {
