@@ -15,11 +15,11 @@
 // is filled by LDS-direct loads (global_load_lds_dwordx4: every lane names a
 // 16 B chunk in global memory, the wave's 64 chunks land in one contiguous
 // 1 KB block of LDS), two k-steps ahead of its use: no staging registers, no
-// LDS store instructions, and a full k-step of slack for the memory latency.
-// A stage keeps the activation tile in "fragment order" (per 16-row sub-tile:
-// 2 halves x 64 lanes x 16 B, lane = 16*(k/16 % 4) + row) so that every operand
-// read is a conflict-free 16 B/lane read; the weight tile already has that
-// order in memory and is copied as is.
+// LDS store instructions, and two k-steps of slack for the memory latency.
+// A stage keeps the activation tile as rows of 128 B with XOR-swizzled 16 B
+// chunks (whole cache lines on the way in, conflict-free 16 B/lane operand
+// reads on the way out); the weight tile already has its operand order in
+// memory and is copied as is.
 #include <type_traits>
 
 #include "zqfp_internal.h"
@@ -113,10 +113,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
 
     // ---- load addresses: uniform base pointers plus 32-bit per-lane offsets.  Rows past M
     // and strips past the last one are clamped to the last valid one: what they produce is
-    // never stored.  Chunk (wave, i) of the activation tile is the 1 KB block (sub-tile
-    // wave/2 + (THREADS/128)*i, half wave%2): lane l fetches row l%16, bytes 16*(l/16 + 4*half)
-    // + [0,16) of the k-tile.  Chunk (wave, i) of the weight tile is strip wave + (THREADS/64)*i,
-    // 1 KB contiguous in memory.
+    // never stored.  Load (wave, i) of the activation tile covers the 8 rows wave*8 + THREADS/8*i
+    // + [0,8): lane l fetches 16 bytes of row l/8, so that 8 consecutive lanes fetch one whole 128 B
+    // line, and the wave's 1 KB lands as 8 rows of 128 B.  Within a row the 16-byte chunks are
+    // XOR-swizzled with the row number (slot s of row r holds chunk s ^ (r % 8)): the operand
+    // reads (lane = (row, k/16 % 4), 16 B each) then spread over all LDS banks.  Load (wave, i) of
+    // the weight tile is strip wave + (THREADS/64)*i, 1 KB contiguous in memory.
     const uint8_t* a_base = Xq + m0 * L.K;                    // uniform
     const uint8_t* b_base = blob + L.off_codes;               // uniform
     const uint8_t* e_base = blob + L.off_exps;                // uniform
@@ -124,9 +126,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     uint32_t a_off[C::A_CHUNKS], b_off[C::B_CHUNKS];
 #pragma unroll
     for (int i = 0; i < C::A_CHUNKS; ++i) {
-        const int cidx = tid + kThreads * i;
-        const int r = cidx & 15, j = (cidx >> 4) & 7, sub = cidx >> 7;
-        a_off[i] = (uint32_t)(min(sub * 16 + r, rows_here - 1) * (int)L.K + 16 * j);
+        const int row = (wave + (kThreads / 64) * i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ (row & 7);
+        a_off[i] = (uint32_t)(min(row, rows_here - 1) * (int)L.K + 16 * chunk);
     }
 #pragma unroll
     for (int i = 0; i < C::B_CHUNKS; ++i) {
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     const uint32_t e_off = 4u * ((uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15));
     // LDS byte addresses (the dynamic array is the kernel's only LDS object)
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
-    const uint32_t a_dst = lds0 + ((wave >> 1) * 2048 + (wave & 1) * 1024);
+    const uint32_t a_dst = lds0 + wave * 1024;
     const uint32_t b_dst = lds0 + C::A_BYTES + wave * 1024;
     const uint32_t e_dst = lds0 + C::A_BYTES + C::B_BYTES + wave * 256;
 
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // t-th load of k-tile kt into LDS stage `stage`
     auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) {
         const uint32_t st = (uint32_t)stage * C::STAGE;
-        if (t < C::A_CHUNKS) lds_load16(a_base + kt * 128, a_off[t], st + a_dst + t * (kThreads / 128) * 2048);
+        if (t < C::A_CHUNKS) lds_load16(a_base + kt * 128, a_off[t], st + a_dst + t * (kThreads / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
             lds_load16(b_base + (int64_t)kt * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kThreads / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
@@ -178,46 +180,69 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
 #pragma unroll
         for (int j = 0; j < WTN; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
+    // ---- operand registers.  They are refilled in place: a weight fragment and its exponent dword
+    // as soon as the last matrix instruction that reads them has been issued, the activation
+    // fragment one row block ahead of its use.
+    v8i bfr[WTN];
+    uint32_t e_cur[WTN];
+    u32x4 a0, a1;
+    GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
+    // this lane's two 16-byte slots inside a 16-row sub-tile (rows of 128 B, chunks XOR-swizzled)
+    const int a_rd0 = col * 128 + ((lb ^ (col & 7)) * 16), a_rd1 = col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
+    auto stage_a = [&](int stage) { return smem + stage * C::STAGE + (wm * WTM) * 2048; };
+    auto stage_b = [&](int stage) { return smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16; };
+    auto stage_e = [&](int stage) {
+        return reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) + wn * WTN * 16 + col;
+    };
+    auto read_b = [&](int j, const uint8_t* sb, const uint32_t* se) {
+        e_cur[j] = se[j * 16];  // raw dword: this lane's byte is shifted down at the top of the step
+        const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
+        bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+    };
+
     // ---- one k-step: the matrix instructions of k-tile kt on LDS stage `stage`.  In-order issue
     // means that whatever a wave puts between two matrix instructions runs in the shadow of the
-    // matrix pipe; so, when LOAD is set, the loads of k-tile kt + 2 into the stage that the previous
-    // step has just released are dealt out one per matrix instruction, and the scheduling fences
-    // pin that order.  The body has no branches.
-    GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
-    auto k_step = [&](int kt, int stage, int stage_load, auto load_tag) {
+    // matrix pipe, and whatever it puts after the last one waits for all of them; the scheduling
+    // fences pin the order written here.  The step's barrier sits BEFORE its last row block: by then
+    // every read of this stage has been issued (the last activation fragment is fetched one block
+    // ahead), so behind the barrier the stage is free, and the next stage is complete.  The last
+    // row block then carries, one per matrix instruction, the requests for k-tile kt + 3 into the
+    // freed stage (LOAD) and the reads of the next step's first operands (NEXT): the matrix pipe
+    // never waits for LDS at the top of a step.  WAIT is the number of this wave's loads that may
+    // still be outstanding at the barrier (those of k-tile kt + 2).  The body has no branches.
+    auto k_step = [&](int kt, int stage, auto load_tag, auto next_tag, auto wait_tag) {
         constexpr bool LOAD = decltype(load_tag)::value;
-        const uint8_t* sa = smem + stage * C::STAGE + (wm * WTM) * 2048 + lane * 16;
-        const uint8_t* sb = smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
+        constexpr bool NEXT = decltype(next_tag)::value;
+        constexpr int WAIT = decltype(wait_tag)::value;
+        const int stage_next = stage == C::NSTAGE - 1 ? 0 : stage + 1;
+        const uint8_t* sa = stage_a(stage);
+        const uint8_t* sa_next = stage_a(stage_next);
+        const uint8_t* sb_next = stage_b(stage_next);
+        const uint32_t* se_next = stage_e(stage_next);
         // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
-        const uint32_t* se = reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) +
-                             wn * WTN * 16 + col;
         const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);
-        // LDS answers in order: exponents and the first fragments first, so that the first matrix
-        // instruction can start while the other weight fragments are still arriving
-        v8i bfr[WTN];
-        uint32_t e_cur[WTN];
 #pragma unroll
-        for (int j = 0; j < WTN; ++j) e_cur[j] = se[j * 16] >> esh;
-        u32x4 a0 = *reinterpret_cast<const u32x4*>(sa);
-        u32x4 a1 = *reinterpret_cast<const u32x4*>(sa + 1024);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < WTN; ++j) {
-            const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
-            bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < WTN; ++j) e_cur[j] >>= esh;
+        constexpr int PASSES = EXACT ? 2 : 1;
 #pragma unroll
         for (int i = 0; i < WTM; ++i) {
+            const bool last_block = i == WTM - 1;
+            if (last_block && NEXT) {
+                __builtin_amdgcn_sched_barrier(0);
+                wait_loads_then_barrier<WAIT>();
+                __builtin_amdgcn_sched_barrier(0);
+            }
             v8i afr = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
-            if (i + 1 < WTM) {  // next activation fragment, one block of matrix instructions ahead
-                a0 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048);
-                a1 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + 1024);
+            if (!last_block) {  // next activation fragment, one block of matrix instructions ahead
+                a0 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + a_rd0);
+                a1 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + a_rd1);
+            } else if (NEXT) {
+                a0 = *reinterpret_cast<const u32x4*>(sa_next + a_rd0);
+                a1 = *reinterpret_cast<const u32x4*>(sa_next + a_rd1);
             }
             v8i hi, lo;
             if constexpr (EXACT) split_exponent_bands(afr, hi, lo);
             __builtin_amdgcn_sched_barrier(0);
-            constexpr int PASSES = EXACT ? 2 : 1;
 #pragma unroll
             for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
@@ -225,53 +250,77 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
                     const v8i& op = EXACT ? (p == 0 ? hi : lo) : afr;
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
                                                                                   (int)e_cur[j]);
-                    const int t = (i * PASSES + p) * WTN + j;  // position in the step's matrix-instruction stream
-                    if (LOAD && t < NSIDE) side_load(t, kt + 2, stage_load, cur_load);
+                    if (last_block) {
+                        const int t = p * WTN + j;  // position in the block's matrix-instruction stream
+                        constexpr int PER = (NSIDE + WTN * PASSES - 1) / (WTN * PASSES);  // loads per slot
+#pragma unroll
+                        for (int q = 0; q < PER; ++q)
+                            if (LOAD && t * PER + q < NSIDE) side_load(t * PER + q, kt + 3, stage, cur_load);
+                        if (NEXT && p == PASSES - 1) read_b(j, sb_next, se_next);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
-        static_assert(WTM * WTN >= NSIDE, "not enough matrix instructions to carry the loads");
         advance(cur_comp);
         if (LOAD) advance(cur_load);
     };
 
-    // ---- prologue: k-tiles 0 and 1 into stages 0 and 1
+    // ---- prologue: k-tiles 0, 1 and 2 into stages 0, 1 and 2; the first operands into registers
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
 #pragma unroll
     for (int t = 0; t < NSIDE; ++t) side_load(t, 0, 0, cur_load);
     if (nkt > 1) {
         advance(cur_load);
 #pragma unroll
         for (int t = 0; t < NSIDE; ++t) side_load(t, 1, 1, cur_load);
-        advance(cur_load);  // now at k-tile 2
-        wait_loads_then_barrier<NSIDE>();  // k-tile 0 has landed, for every wave
-    } else {
-        wait_loads_then_barrier<0>();
+    }
+    if (nkt > 2) {
+        advance(cur_load);
+#pragma unroll
+        for (int t = 0; t < NSIDE; ++t) side_load(t, 2, 2, cur_load);
+        advance(cur_load);  // now at k-tile 3
+    }
+    // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done
+    if (nkt > 2) wait_loads_then_barrier<2 * NSIDE>();
+    else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
+    else wait_loads_then_barrier<0>();
+    {
+        const uint8_t* sa = stage_a(0);
+        const uint8_t* sb = stage_b(0);
+        const uint32_t* se = stage_e(0);
+        a0 = *reinterpret_cast<const u32x4*>(sa + a_rd0);
+        a1 = *reinterpret_cast<const u32x4*>(sa + a_rd1);
+#pragma unroll
+        for (int j = 0; j < WTN; ++j) read_b(j, sb, se);
     }
 
-    // ---- main loop.  Step kt computes stage kt % 3 while k-tile kt + 1 is landing in the next stage
-    // and k-tile kt + 2 is being requested into the third, which every wave stopped reading at the
-    // barrier that ended step kt - 1.  Before the barrier that ends step kt each wave waits for all
-    // of its loads but this step's NSIDE: then k-tile kt + 1 is complete once every wave is through.
-    // The last two steps request nothing and are peeled, so the loop body stays free of branches.
-    using with_loads = std::integral_constant<bool, true>;
-    using no_loads = std::integral_constant<bool, false>;
-    int stage = 0, stage_load = 2;
+    // ---- main loop.  Step kt computes stage kt % 3; k-tiles kt + 1 and kt + 2 are in the other two
+    // stages or on their way, k-tile kt + 3 is requested into stage kt % 3 behind the step's
+    // barrier.  At that barrier each wave waits for all of its loads but the NSIDE of k-tile
+    // kt + 2: then k-tile kt + 1 is complete once every wave is through, after two steps of slack
+    // for the memory latency.  The last three steps request nothing and are peeled.
+    using W1 = std::integral_constant<int, NSIDE>;
+    using W0 = std::integral_constant<int, 0>;
+    int stage = 0;
     auto next = [](int st) { return st == C::NSTAGE - 1 ? 0 : st + 1; };
     int kt = 0;
-    for (; kt + 2 < nkt; ++kt) {
-        k_step(kt, stage, stage_load, with_loads{});
-        wait_loads_then_barrier<NSIDE>();
+    for (; kt + 3 < nkt; ++kt) {
+        k_step(kt, stage, yes{}, yes{}, W1{});
         stage = next(stage);
-        stage_load = next(stage_load);
     }
-    if (nkt > 1) {
-        k_step(kt, stage, stage_load, no_loads{});
-        wait_loads_then_barrier<0>();
+    if (nkt > 2) {  // kt == nkt - 3: k-tile kt + 2 still outstanding
+        k_step(kt, stage, no{}, yes{}, W1{});
         stage = next(stage);
         ++kt;
     }
-    k_step(kt, stage, stage_load, no_loads{});
+    if (nkt > 1) {  // kt == nkt - 2
+        k_step(kt, stage, no{}, yes{}, W0{});
+        stage = next(stage);
+        ++kt;
+    }
+    k_step(kt, stage, no{}, no{}, W0{});
 
     // ---- epilogue.  D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4:
     // good for the scale / LoRC arithmetic (one column per lane), bad for stores (64 B runs).
