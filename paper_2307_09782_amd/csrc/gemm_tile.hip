@@ -185,7 +185,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // fragment one row block ahead of its use.
     v8i bfr[WTN];
     uint32_t e_cur[WTN];
-    u32x4 a0, a1;
+    // Activation fragments rotate through two registers sets: row block i multiplies one (fy for
+    // even i, fz for odd i) while the next fragment arrives in the other.  In the exact mode the
+    // multiplied set holds the lower exponent band and fx the upper one; the arriving fragment is
+    // split in place, one dword per matrix instruction of the lower-band pass, into fx (whose old
+    // content the upper-band pass has already consumed) and itself.
+    v8i fx, fy, fz;
     GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
     // this lane's two 16-byte slots inside a 16-row sub-tile (rows of 128 B, chunks XOR-swizzled)
     const int a_rd0 = col * 128 + ((lb ^ (col & 7)) * 16), a_rd1 = col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
@@ -195,9 +200,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         return reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) + wn * WTN * 16 + col;
     };
     auto read_b = [&](int j, const uint8_t* sb, const uint32_t* se) {
-        e_cur[j] = se[j * 16];  // raw dword: this lane's byte is shifted down at the top of the step
+        e_cur[j] = se[j * 16];  // raw dword: this lane's byte is shifted down at its first use
         const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
         bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+    };
+    auto read_a = [&](v8i& dst, const uint8_t* sub_tile) {
+        const u32x4 p = *reinterpret_cast<const u32x4*>(sub_tile + a_rd0);
+        const u32x4 q = *reinterpret_cast<const u32x4*>(sub_tile + a_rd1);
+        dst = (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
+    };
+    auto split_in_place = [&](v8i& frag, int d) {  // dword d of frag -> upper band into fx, lower band stays
+        uint32_t h, l;
+        split_exponent_bands_dword((uint32_t)frag[d], h, l);
+        fx[d] = (int)h;
+        frag[d] = (int)l;
     };
 
     // ---- one k-step: the matrix instructions of k-tile kt on LDS stage `stage`.  In-order issue
@@ -221,8 +237,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         const uint32_t* se_next = stage_e(stage_next);
         // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
         const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);
-#pragma unroll
-        for (int j = 0; j < WTN; ++j) e_cur[j] >>= esh;
         constexpr int PASSES = EXACT ? 2 : 1;
 #pragma unroll
         for (int i = 0; i < WTM; ++i) {
@@ -232,24 +246,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
                 wait_loads_then_barrier<WAIT>();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            v8i afr = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
-            if (!last_block) {  // next activation fragment, one block of matrix instructions ahead
-                a0 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + a_rd0);
-                a1 = *reinterpret_cast<const u32x4*>(sa + (i + 1) * 2048 + a_rd1);
-            } else if (NEXT) {
-                a0 = *reinterpret_cast<const u32x4*>(sa_next + a_rd0);
-                a1 = *reinterpret_cast<const u32x4*>(sa_next + a_rd1);
-            }
-            v8i hi, lo;
-            if constexpr (EXACT) split_exponent_bands(afr, hi, lo);
+            v8i& cur = (i & 1) ? fz : fy;
+            v8i& inc = (i & 1) ? fy : fz;
+            const bool fetch = !last_block || NEXT;
+            if (!last_block) read_a(inc, sa + (i + 1) * 2048);  // one block of matrix instructions ahead
+            else if (NEXT) read_a(inc, sa_next);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
                 for (int j = 0; j < WTN; ++j) {
-                    const v8i& op = EXACT ? (p == 0 ? hi : lo) : afr;
+                    const v8i& op = (EXACT && p == 0) ? fx : cur;
+                    if (i == 0 && p == 0) e_cur[j] >>= esh;  // at its first use: the dword was the last thing read
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
                                                                                   (int)e_cur[j]);
+                    if (EXACT && p == 1 && fetch) {
+#pragma unroll
+                        for (int d = j * 8 / WTN; d < (j + 1) * 8 / WTN; ++d) split_in_place(inc, d);
+                    }
                     if (last_block) {
                         const int t = p * WTN + j;  // position in the block's matrix-instruction stream
                         constexpr int PER = (NSIDE + WTN * PASSES - 1) / (WTN * PASSES);  // loads per slot
@@ -262,6 +276,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
                 }
             }
         }
+        static_assert(WTM % 2 == 0 && 8 % WTN == 0, "fragment rotation and split slots assume these");
         advance(cur_comp);
         if (LOAD) advance(cur_load);
     };
@@ -287,13 +302,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
     else wait_loads_then_barrier<0>();
     {
-        const uint8_t* sa = stage_a(0);
         const uint8_t* sb = stage_b(0);
         const uint32_t* se = stage_e(0);
-        a0 = *reinterpret_cast<const u32x4*>(sa + a_rd0);
-        a1 = *reinterpret_cast<const u32x4*>(sa + a_rd1);
+        read_a(fy, stage_a(0));
 #pragma unroll
         for (int j = 0; j < WTN; ++j) read_b(j, sb, se);
+        if constexpr (EXACT) {
+#pragma unroll
+            for (int d = 0; d < 8; ++d) split_in_place(fy, d);
+        }
     }
 
     // ---- main loop.  Step kt computes stage kt % 3; k-tiles kt + 1 and kt + 2 are in the other two

@@ -85,15 +85,20 @@ __device__ inline float half_bits_to_f32(uint16_t h) { return (float)__builtin_b
 // v_perm_b32 replicate bit 15 or bit 31 of a source over a byte, and x << 9 / x << 1 put bit 6
 // of bytes 0, 2 / 1, 3 there.  Five full-rate operations per dword.
 typedef int zq_v8i __attribute__((ext_vector_type(8)));
+__device__ inline void split_exponent_bands_dword(uint32_t x, uint32_t& hi, uint32_t& lo)
+{
+    const uint32_t m = __builtin_amdgcn_perm(x << 1, x << 9, 0x0B090A08u);
+    hi = x & m;
+    lo = x ^ hi;
+}
 __device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i& lo)
 {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint32_t x = (uint32_t)a[i];
-        const uint32_t m = __builtin_amdgcn_perm(x << 1, x << 9, 0x0B090A08u);
-        const uint32_t h = x & m;
+        uint32_t h, l;
+        split_exponent_bands_dword((uint32_t)a[i], h, l);
         hi[i] = (int)h;
-        lo[i] = (int)(x ^ h);
+        lo[i] = (int)l;
     }
 }
 
