@@ -50,6 +50,47 @@ __device__ inline void lds_load4(const uint8_t* gbase, uint32_t voff, uint32_t l
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
 }
+// LDS reads issued by hand: the result registers are valid only after a wait_lds that names them
+// (LDS answers a wave's requests in order; the compiler neither sees these reads nor waits for them).
+template <int OFF>
+__device__ inline u32x4 lds_read16(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF>
+__device__ inline uint32_t lds_read4(uint32_t addr)
+{
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// Waits until at most N of this wave's LDS reads are outstanding; the registers named are the ones
+// whose use must follow the wait.
+template <int N>
+__device__ inline void wait_lds(u32x4& a, uint32_t& b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N>
+__device__ inline void wait_lds(u32x4& a, u32x4& b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N>
+__device__ inline void wait_lds(u32x4& a, uint32_t& b, u32x4& c, u32x4& d)
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
 // Waits until at most N of this wave's loads are outstanding (loads complete in order) and for
 // its LDS traffic, then joins the workgroup barrier.
 template <int N>
@@ -165,7 +206,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // ---- one stage = NSIDE loads per wave: A_CHUNKS + B_CHUNKS 1 KB blocks and 256 B of exponents
     constexpr int NSIDE = C::A_CHUNKS + C::B_CHUNKS + 1;
     // t-th load of k-tile kt into LDS stage `stage`
-    auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) {
+    auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) __attribute__((always_inline)) {
         const uint32_t st = (uint32_t)stage * C::STAGE;
         if (t < C::A_CHUNKS) lds_load16(a_base + kt * 128, a_off[t], st + a_dst + t * (kThreads / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
@@ -182,108 +223,125 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
 
     // ---- operand registers.  They are refilled in place: a weight fragment and its exponent dword
     // as soon as the last matrix instruction that reads them has been issued, the activation
-    // fragment one row block ahead of its use.
-    v8i bfr[WTN];
-    uint32_t e_cur[WTN];
-    // Activation fragments rotate through two registers sets: row block i multiplies one (fy for
-    // even i, fz for odd i) while the next fragment arrives in the other.  In the exact mode the
-    // multiplied set holds the lower exponent band and fx the upper one; the arriving fragment is
-    // split in place, one dword per matrix instruction of the lower-band pass, into fx (whose old
-    // content the upper-band pass has already consumed) and itself.
+    // fragment almost a row block ahead of its use.  Activation fragments rotate through two
+    // register sets: row block i multiplies one (fy for even i, fz for odd i) while the next
+    // fragment arrives (ta, tb) and becomes the other.  In the exact mode the multiplied set holds
+    // the lower exponent band and fx the upper one; the arrived fragment is split in place, one
+    // dword per matrix instruction of the lower-band pass, into fx (whose old content the
+    // upper-band pass has already consumed) and itself.
+    u32x4 bq[WTN];        // weight fragments
+    uint32_t e_cur[WTN];  // their exponent dwords (raw until the first use in a step)
     v8i fx, fy, fz;
+    u32x4 ta, tb;         // the activation fragment in flight
     GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
-    // this lane's two 16-byte slots inside a 16-row sub-tile (rows of 128 B, chunks XOR-swizzled)
-    const int a_rd0 = col * 128 + ((lb ^ (col & 7)) * 16), a_rd1 = col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
-    auto stage_a = [&](int stage) { return smem + stage * C::STAGE + (wm * WTM) * 2048; };
-    auto stage_b = [&](int stage) { return smem + stage * C::STAGE + C::A_BYTES + (wn * WTN) * 1024 + lane * 16; };
-    auto stage_e = [&](int stage) {
-        return reinterpret_cast<const uint32_t*>(smem + stage * C::STAGE + C::A_BYTES + C::B_BYTES) + wn * WTN * 16 + col;
+    // per-lane LDS addresses inside stage 0 (the stage offset is added per step)
+    const uint32_t a_addr0 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7)) * 16);
+    const uint32_t a_addr1 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
+    const uint32_t b_addr = lds0 + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
+    const uint32_t e_addr = lds0 + C::A_BYTES + C::B_BYTES + (wn * WTN * 16 + col) * 4;
+    auto as_v8i = [](const u32x4& p, const u32x4& q) {
+        return (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
     };
-    auto read_b = [&](int j, const uint8_t* sb, const uint32_t* se) {
-        e_cur[j] = se[j * 16];  // raw dword: this lane's byte is shifted down at its first use
-        const u32x4 b = *reinterpret_cast<const u32x4*>(sb + j * 1024);
-        bfr[j] = (v8i){(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
-    };
-    auto read_a = [&](v8i& dst, const uint8_t* sub_tile) {
-        const u32x4 p = *reinterpret_cast<const u32x4*>(sub_tile + a_rd0);
-        const u32x4 q = *reinterpret_cast<const u32x4*>(sub_tile + a_rd1);
-        dst = (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
-    };
-    auto split_in_place = [&](v8i& frag, int d) {  // dword d of frag -> upper band into fx, lower band stays
+    auto split_in_place = [&](v8i& frag, int d) __attribute__((always_inline)) {  // dword d of frag -> upper band into fx, lower band stays
         uint32_t h, l;
         split_exponent_bands_dword((uint32_t)frag[d], h, l);
         fx[d] = (int)h;
         frag[d] = (int)l;
     };
+    constexpr int PASSES = EXACT ? 2 : 1;
+    static_assert(WTM % 2 == 0 && 8 % WTN == 0 && WTN >= 4, "fragment rotation, split slots and wait schedule assume these");
 
-    // ---- one k-step: the matrix instructions of k-tile kt on LDS stage `stage`.  In-order issue
-    // means that whatever a wave puts between two matrix instructions runs in the shadow of the
-    // matrix pipe, and whatever it puts after the last one waits for all of them; the scheduling
-    // fences pin the order written here.  The step's barrier sits BEFORE its last row block: by then
-    // every read of this stage has been issued (the last activation fragment is fetched one block
-    // ahead), so behind the barrier the stage is free, and the next stage is complete.  The last
-    // row block then carries, one per matrix instruction, the requests for k-tile kt + 3 into the
-    // freed stage (LOAD) and the reads of the next step's first operands (NEXT): the matrix pipe
-    // never waits for LDS at the top of a step.  WAIT is the number of this wave's loads that may
-    // still be outstanding at the barrier (those of k-tile kt + 2).  The body has no branches.
-    auto k_step = [&](int kt, int stage, auto load_tag, auto next_tag, auto wait_tag) {
+    // ---- one row block of a k-step: WTN (x2 in the exact mode) matrix instructions on row block I
+    // of k-tile kt, whose stage starts at LDS offset st.  In-order issue means that whatever a
+    // wave puts between two matrix instructions runs in the shadow of the matrix pipe; the
+    // scheduling fences pin the order written here.  LDS reads are issued and waited for by hand:
+    // LDS answers in order, so "at most N reads outstanding" names exactly which have arrived.
+    //   * behind the block's second instruction: the request for the next activation fragment
+    //     (row block I + 1, or row block 0 of the next stage st_next when I is the last and NEXT);
+    //   * last block only (it runs behind the step's barrier, see below): one per instruction, the
+    //     requests for k-tile kt + 3 into this step's stage (LOAD) and, behind the last instruction
+    //     that reads them, the next step's weight fragments and exponent dwords (NEXT);
+    //   * block 0: instruction j waits for its own fragment j only (read_b order: e0 b0 e1 b1 ...):
+    //     2 (WTN - 1 - j) younger reads, plus the 2 of the activation request once that is out.
+    auto row_block = [&](auto i_tag, int kt, uint32_t st, uint32_t st_next, int stage, auto load_tag, auto next_tag) __attribute__((always_inline)) {
+        constexpr int I = decltype(i_tag)::value;
         constexpr bool LOAD = decltype(load_tag)::value;
         constexpr bool NEXT = decltype(next_tag)::value;
-        constexpr int WAIT = decltype(wait_tag)::value;
-        const int stage_next = stage == C::NSTAGE - 1 ? 0 : stage + 1;
-        const uint8_t* sa = stage_a(stage);
-        const uint8_t* sa_next = stage_a(stage_next);
-        const uint8_t* sb_next = stage_b(stage_next);
-        const uint32_t* se_next = stage_e(stage_next);
-        // this lane's exponent byte for each of its WTN columns: byte (stored group & 3) of the dword
-        const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);
-        constexpr int PASSES = EXACT ? 2 : 1;
-#pragma unroll
-        for (int i = 0; i < WTM; ++i) {
-            const bool last_block = i == WTM - 1;
-            if (last_block && NEXT) {
-                __builtin_amdgcn_sched_barrier(0);
-                wait_loads_then_barrier<WAIT>();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            v8i& cur = (i & 1) ? fz : fy;
-            v8i& inc = (i & 1) ? fy : fz;
-            const bool fetch = !last_block || NEXT;
-            if (!last_block) read_a(inc, sa + (i + 1) * 2048);  // one block of matrix instructions ahead
-            else if (NEXT) read_a(inc, sa_next);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int p = 0; p < PASSES; ++p) {
-#pragma unroll
-                for (int j = 0; j < WTN; ++j) {
-                    const v8i& op = (EXACT && p == 0) ? fx : cur;
-                    if (i == 0 && p == 0) e_cur[j] >>= esh;  // at its first use: the dword was the last thing read
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bfr[j], acc[i][j], 0, 4, 0, 127, 0,
-                                                                                  (int)e_cur[j]);
-                    if (EXACT && p == 1 && fetch) {
-#pragma unroll
-                        for (int d = j * 8 / WTN; d < (j + 1) * 8 / WTN; ++d) split_in_place(inc, d);
+        constexpr bool last_block = I == WTM - 1;
+        constexpr bool fetch = !last_block || NEXT;
+        v8i& cur = (I & 1) ? fz : fy;
+        v8i& inc = (I & 1) ? fy : fz;
+        const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);  // this lane's exponent byte: (stored group & 3) of the dword
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, PASSES>([&](auto p_tag) __attribute__((always_inline)) {
+            constexpr int P = decltype(p_tag)::value;
+            static_for<0, WTN>([&](auto j_tag) __attribute__((always_inline)) {
+                constexpr int J = decltype(j_tag)::value;
+                if constexpr (I == 0 && P == 0) {
+                    constexpr int YOUNGER = 2 * (WTN - 1 - J) + (J >= 2 ? 2 : 0);
+                    if constexpr (J == 0 && !EXACT) {  // the fragment that arrived during the previous block
+                        wait_lds<YOUNGER>(bq[J], e_cur[J], ta, tb);
+                        cur = as_v8i(ta, tb);
+                    } else {
+                        wait_lds<YOUNGER>(bq[J], e_cur[J]);
                     }
-                    if (last_block) {
-                        const int t = p * WTN + j;  // position in the block's matrix-instruction stream
-                        constexpr int PER = (NSIDE + WTN * PASSES - 1) / (WTN * PASSES);  // loads per slot
-#pragma unroll
-                        for (int q = 0; q < PER; ++q)
-                            if (LOAD && t * PER + q < NSIDE) side_load(t * PER + q, kt + 3, stage, cur_load);
-                        if (NEXT && p == PASSES - 1) read_b(j, sb_next, se_next);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                    e_cur[J] >>= esh;
+                } else if constexpr (I > 0 && P == 0 && J == 0 && !EXACT) {
+                    wait_lds<0>(ta, tb);
+                    cur = as_v8i(ta, tb);
                 }
-            }
-        }
-        static_assert(WTM % 2 == 0 && 8 % WTN == 0, "fragment rotation and split slots assume these");
-        advance(cur_comp);
-        if (LOAD) advance(cur_load);
+                if constexpr (EXACT && P == 1 && J == 0 && fetch) {
+                    wait_lds<0>(ta, tb);
+                    inc = as_v8i(ta, tb);
+                }
+                const v8i& op = (EXACT && P == 0) ? fx : cur;
+                const v8i bv = {(int)bq[J][0], (int)bq[J][1], (int)bq[J][2], (int)bq[J][3], 0, 0, 0, 0};
+                // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
+                acc[I][J] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bv, acc[I][J], 0, 4, 0, 127, 0, (int)e_cur[J]);
+                if constexpr (P == 0 && J == 1 && fetch) {
+                    if constexpr (!last_block) {
+                        ta = lds_read16<(I + 1) * 2048>(a_addr0 + st);
+                        tb = lds_read16<(I + 1) * 2048>(a_addr1 + st);
+                    } else {
+                        ta = lds_read16<0>(a_addr0 + st_next);
+                        tb = lds_read16<0>(a_addr1 + st_next);
+                    }
+                }
+                if constexpr (EXACT && P == 1 && fetch) {
+#pragma unroll
+                    for (int d = J * 8 / WTN; d < (J + 1) * 8 / WTN; ++d) split_in_place(inc, d);
+                }
+                if constexpr (last_block) {
+                    constexpr int T = P * WTN + J;  // position in the block's matrix-instruction stream
+                    constexpr int PER = (NSIDE + WTN * PASSES - 1) / (WTN * PASSES);  // loads per slot
+#pragma unroll
+                    for (int q = 0; q < PER; ++q)
+                        if (LOAD && T * PER + q < NSIDE) side_load(T * PER + q, kt + 3, stage, cur_load);
+                    if constexpr (NEXT && P == PASSES - 1) {
+                        e_cur[J] = lds_read4<J * 64>(e_addr + st_next);
+                        bq[J] = lds_read16<J * 1024>(b_addr + st_next);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    auto stage_off = [](int stage) { return (uint32_t)stage * C::STAGE; };
+    auto next = [](int st) { return st == C::NSTAGE - 1 ? 0 : st + 1; };
+    // row blocks 0 .. WTM - 2 of step kt, then the step's barrier.  It sits BEFORE the last row
+    // block: by then every read of this stage has been issued (the last activation fragment is
+    // requested one block ahead), so behind the barrier the stage is free for k-tile kt + 3, and
+    // the next stage is complete: each wave has waited for all of its loads but the WAIT that may
+    // belong to k-tile kt + 2.
+    auto head_blocks = [&](int kt, int stage, auto wait_tag) __attribute__((always_inline)) {
+        const uint32_t st = stage_off(stage);
+        static_for<0, WTM - 1>([&](auto i_tag) __attribute__((always_inline)) { row_block(i_tag, kt, st, 0u, stage, no{}, no{}); });
+        wait_loads_then_barrier<decltype(wait_tag)::value>();
     };
 
     // ---- prologue: k-tiles 0, 1 and 2 into stages 0, 1 and 2; the first operands into registers
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
 #pragma unroll
     for (int t = 0; t < NSIDE; ++t) side_load(t, 0, 0, cur_load);
     if (nkt > 1) {
@@ -301,43 +359,46 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     if (nkt > 2) wait_loads_then_barrier<2 * NSIDE>();
     else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
     else wait_loads_then_barrier<0>();
-    {
-        const uint8_t* sb = stage_b(0);
-        const uint32_t* se = stage_e(0);
-        read_a(fy, stage_a(0));
+    ta = lds_read16<0>(a_addr0);
+    tb = lds_read16<0>(a_addr1);
+    static_for<0, WTN>([&](auto j_tag) __attribute__((always_inline)) {
+        constexpr int J = decltype(j_tag)::value;
+        e_cur[J] = lds_read4<J * 64>(e_addr);
+        bq[J] = lds_read16<J * 1024>(b_addr);
+    });
+    if constexpr (EXACT) {  // the fast mode picks ta, tb up at its first matrix instruction
+        wait_lds<(2 * WTN < 15 ? 2 * WTN : 15)>(ta, tb);  // the counter holds 15 at most
+        fy = as_v8i(ta, tb);
 #pragma unroll
-        for (int j = 0; j < WTN; ++j) read_b(j, sb, se);
-        if constexpr (EXACT) {
-#pragma unroll
-            for (int d = 0; d < 8; ++d) split_in_place(fy, d);
-        }
+        for (int d = 0; d < 8; ++d) split_in_place(fy, d);
     }
 
     // ---- main loop.  Step kt computes stage kt % 3; k-tiles kt + 1 and kt + 2 are in the other two
     // stages or on their way, k-tile kt + 3 is requested into stage kt % 3 behind the step's
-    // barrier.  At that barrier each wave waits for all of its loads but the NSIDE of k-tile
-    // kt + 2: then k-tile kt + 1 is complete once every wave is through, after two steps of slack
-    // for the memory latency.  The last three steps request nothing and are peeled.
+    // barrier, two steps of slack for the memory latency.  The loop is rotated so that no LDS read
+    // is in flight across its back edge: an iteration is the last row block of step kt followed by
+    // the first blocks of step kt + 1 and that step's barrier.  The last steps request nothing
+    // and are peeled.
     using W1 = std::integral_constant<int, NSIDE>;
     using W0 = std::integral_constant<int, 0>;
     int stage = 0;
-    auto next = [](int st) { return st == C::NSTAGE - 1 ? 0 : st + 1; };
+    if (nkt > 2) head_blocks(0, 0, W1{});
+    else head_blocks(0, 0, W0{});
     int kt = 0;
-    for (; kt + 3 < nkt; ++kt) {
-        k_step(kt, stage, yes{}, yes{}, W1{});
+    for (; kt + 3 < nkt; ++kt) {  // k-tiles kt + 2 and kt + 3 exist
+        row_block(std::integral_constant<int, WTM - 1>{}, kt, stage_off(stage), stage_off(next(stage)), stage, yes{}, yes{});
+        advance(cur_comp);
+        advance(cur_load);
         stage = next(stage);
+        head_blocks(kt + 1, stage, W1{});
     }
-    if (nkt > 2) {  // kt == nkt - 3: k-tile kt + 2 still outstanding
-        k_step(kt, stage, no{}, yes{}, W1{});
+    for (; kt + 1 < nkt; ++kt) {  // nothing left to request: at the barrier no load may be outstanding
+        row_block(std::integral_constant<int, WTM - 1>{}, kt, stage_off(stage), stage_off(next(stage)), stage, no{}, yes{});
+        advance(cur_comp);
         stage = next(stage);
-        ++kt;
+        head_blocks(kt + 1, stage, W0{});
     }
-    if (nkt > 1) {  // kt == nkt - 2
-        k_step(kt, stage, no{}, yes{}, W0{});
-        stage = next(stage);
-        ++kt;
-    }
-    k_step(kt, stage, no{}, no{}, W0{});
+    row_block(std::integral_constant<int, WTM - 1>{}, kt, stage_off(stage), 0u, stage, no{}, no{});
 
     // ---- epilogue.  D[row][col] of a 16x16 tile sits in lane 16*(row/4)+col, register row%4:
     // good for the scale / LoRC arithmetic (one column per lane), bad for stores (64 B runs).
