@@ -27,6 +27,12 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+# Kernels that issue LDS reads by hand (inline asm) and wait for them by count: a register spill
+# between such a read and its wait would save a value that has not arrived yet, so these must
+# compile without scratch memory.  The compiler's resource remarks are checked after every build.
+NO_SCRATCH_KERNELS = ("k_gemm_tile",)
+
+
 def _run(cmd):
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
@@ -35,14 +41,32 @@ def _run(cmd):
     return out
 
 
+def _check_no_scratch(remarks):
+    """Raise if a kernel named in NO_SCRATCH_KERNELS uses scratch memory or spills registers."""
+    name = None
+    for line in remarks.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].split("[")[0].strip()
+        elif name and any(k in name for k in NO_SCRATCH_KERNELS):
+            for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):
+                if text.startswith(key) and int(text[len(key):].split("[")[0]) != 0:
+                    raise RuntimeError(f"{name}: '{text}' -- this kernel must not spill (hand-scheduled LDS reads)")
+
+
 def build_lib(verbose=False, jobs=8):
     """Compile every csrc/*.hip and link libzqfp.so (always recompiles)."""
     os.makedirs(OBJDIR, exist_ok=True)
     srcs = sources()
     objs = [os.path.join(OBJDIR, os.path.basename(s)[:-4] + ".o") for s in srcs]
-    cmds = [[HIPCC, *FLAGS, "-c", s, "-o", o] for s, o in zip(srcs, objs)]
+    cmds = [[HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", s, "-o", o] for s, o in zip(srcs, objs)]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         outs = list(ex.map(_run, cmds))
+    for o in outs:
+        _check_no_scratch(o)
+    outs = ["\n".join(l for l in o.splitlines() if "kernel-resource-usage" not in l and not l.lstrip().startswith(("|", "^")) and not l.strip().split(" ", 1)[0].isdigit()) for o in outs]
     outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
     if verbose:
         text = "\n".join(o for o in outs if o.strip())

@@ -79,3 +79,18 @@ def test_argument_checks_return_error_codes_without_a_gpu(lib):
     assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 8, 0, 0, None, None) == -2
     assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, None, None, 8, p(a16), 16, 0, 0, None, None) == -1
     assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), p(a16), 65, p(a16), 16, 0, 0, None, None) == -2
+
+
+def test_build_rejects_spills_in_hand_scheduled_kernels():
+    """The tiled GEMM waits for its LDS reads by count; the build refuses a compile in which that
+    kernel uses scratch memory (a spill could save a register whose read is still in flight)."""
+    from paper_2307_09782_amd import build
+    ok = ("x.hip:1:1: remark: Function Name: _ZN4zqfp11k_gemm_tileILi4EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark: Function Name: _ZN4zqfp13k_gemm_decodeILi8EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 96 [-Rpass-analysis=kernel-resource-usage]\n")
+    build._check_no_scratch(ok)  # other kernels may use scratch
+    bad = ok.replace("ScratchSize [bytes/lane]: 0", "ScratchSize [bytes/lane]: 24")
+    with pytest.raises(RuntimeError):
+        build._check_no_scratch(bad)
