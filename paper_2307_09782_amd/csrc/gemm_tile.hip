@@ -414,6 +414,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     float cn[WTN];
 #pragma unroll
     for (int j = 0; j < WTN; ++j) cn[j] = colscale[min(n_wave + j * 16 + col, L.Np - 1)];
+    // LoRC of rank <= 8 (the paper's setting): the tile's rows of T and columns of V go through LDS
+    // once (zero-padded to rank 8, V converted to binary32), so that the 8 fused multiply-adds per
+    // output read registers filled by two 16-byte LDS reads per row and per column.
+    constexpr int RL = 8;
+    constexpr int PATCH_BYTES = C::THREADS / 64 * 16 * SLAB_LD * 4;
+    static_assert(PATCH_BYTES + (C::BM + C::BN) * RL * 4 <= C::NSTAGE * C::STAGE, "LoRC tiles do not fit the stages");
+    float* Ts = reinterpret_cast<float*>(smem + PATCH_BYTES);  // [BM][RL]
+    float* Vs = Ts + C::BM * RL;                               // [BN][RL]
+    const int rk = lorc.r;
+    const bool lorc_lds = rk > 0 && rk <= RL;
+    if (lorc_lds) {
+        for (int idx = tid; idx < C::BM * RL; idx += kThreads) {
+            const int row = idx / RL, q = idx % RL;
+            Ts[idx] = q < rk ? lorc.T[min(m0 + row, M - 1) * rk + q] : 0.f;
+        }
+        for (int idx = tid; idx < RL * C::BN; idx += kThreads) {
+            const int q = idx / C::BN, c = idx % C::BN;
+            const int64_t n = min(strip0 * 16 + c, L.N - 1);
+            Vs[c * RL + q] = q < rk ? half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]) : 0.f;
+        }
+        __syncthreads();
+    }
     constexpr int LPR = SLAB_N / 4;   // lanes per slab row when each lane carries 4 columns
     constexpr int RPI = 64 / LPR;     // slab rows per store instruction
     const int srow = lane / LPR, scol = (lane % LPR) * 4;
@@ -424,15 +446,32 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         float sxm[4];
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) sxm[rg] = sx[min(m_slab + 4 * lb + rg, M - 1)];
+        v4f tl[4][RL / 4];
+        if (lorc_lds) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+#pragma unroll
+                for (int h = 0; h < RL / 4; ++h)
+                    tl[rg][h] = *reinterpret_cast<const v4f*>(Ts + ((wm * WTM + i) * 16 + 4 * lb + rg) * RL + 4 * h);
+        }
 #pragma unroll
         for (int j = 0; j < WTN; ++j) {
             const int64_t n = min(n_wave + j * 16 + col, L.N - 1);
+            v4f vl[RL / 4];
+            if (lorc_lds) {
+#pragma unroll
+                for (int h = 0; h < RL / 4; ++h)
+                    vl[h] = *reinterpret_cast<const v4f*>(Vs + ((wn * WTN + j) * 16 + col) * RL + 4 * h);
+            }
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 float y = (sxm[rg] * cn[j]) * acc[i][j][rg];
-                if (lorc.r > 0) {
-                    const float* t = lorc.T + min(m_slab + 4 * lb + rg, M - 1) * lorc.r;
-                    for (int q = 0; q < lorc.r; ++q) y = fmaf(t[q], half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]), y);
+                if (lorc_lds) {
+#pragma unroll
+                    for (int q = 0; q < RL; ++q) y = fmaf(tl[rg][q / 4][q % 4], vl[q / 4][q % 4], y);  // padding adds 0 * 0
+                } else if (rk > 0) {  // larger ranks: read in place
+                    const float* t = lorc.T + min(m_slab + 4 * lb + rg, M - 1) * rk;
+                    for (int q = 0; q < rk; ++q) y = fmaf(t[q], half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]), y);
                 }
                 patch[(4 * lb + rg) * SLAB_LD + j * 16 + col] = y;
             }
@@ -495,15 +534,18 @@ template <bool EXACT>
 hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                        void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
-    // 256 x 256 tiles once they fill the 256 compute units at least ~twice, else 128 x 128
-    const int64_t big = ((M + 255) / 256) * ((L.Np + 255) / 256);
-    if (big >= 384) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
-    return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    // 256 x 256 tiles (8 waves, one workgroup per compute unit) once they fill the 256 compute units
+    // at least ~1.5 times; else 128 x 128 (4 waves, two workgroups per compute unit) under the same
+    // condition; else 64 x 128, which also serves 16 < M <= 64, where the kernel is a weight stream.
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.Np + bn - 1) / bn); };
+    if (tiles(256, 256) >= 384) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    if (M > 64 && tiles(128, 128) >= 384) return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    return launch_cfg<2, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
 }
 
 }  // namespace
 
-bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 64 && L.N >= 64; }
+bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 16 && L.N >= 64; }
 
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
                             Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
