@@ -186,6 +186,41 @@ def calibration_copy(nbytes=1 << 30):
     torch.cuda.empty_cache()
 
 
+def measured_ceilings():
+    """What the device itself sustains right now (measurement probes of the library, timed with HIP
+    events): a plain streaming read of 2 GiB, twice the last-level cache eight times over, and a
+    register-only loop of the FP8 x FP4 matrix instruction on every compute unit."""
+    src = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(3)
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    ops = torch.randint(0, 2 ** 31 - 1, (1024,), dtype=torch.int32, device="cuda")
+    wgs_mfma = 256
+    fsink = torch.zeros(512 * wgs_mfma, dtype=torch.float32, device="cuda")
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    wgs_read = 2048
+    ms_read = timed(lambda: zqfp.probe_stream_read(src, sink, wgs_read), 5)
+    read_bytes = (src.numel() // (wgs_read * 4 * 8 * 1024)) * (wgs_read * 4 * 8 * 1024)
+    iters = 4000
+    flop = [0.0]
+    def mf():
+        flop[0] = zqfp.probe_mfma(ops, fsink, iters, wgs_mfma)
+    ms_mfma = timed(mf, 3)
+    del src
+    torch.cuda.empty_cache()
+    return {"stream_read_gbs": round(read_bytes / (ms_read * 1e-3) / 1e9, 1),
+            "mfma_fp8xfp4_tflops": round(flop[0] / (ms_mfma * 1e-3) / 1e12, 1)}
+
+
 def cpu_baseline(name, M, rows=2048):
     """The CPU oracle on a bounded sample: `rows` tokens of the same workload,
     whole hot path (quantize, LoRC left factor, GEMM over all N)."""
@@ -284,6 +319,11 @@ def main():
             torch.cuda.empty_cache()
         out["also"] = also
 
+    if not args.no_also:
+        ceil = measured_ceilings()
+        rf = out["roofline"]
+        ceil["frac_of_measured"] = round(rf["achieved"] / (ceil["stream_read_gbs"] if rf["bound"] == "hbm" else ceil["mfma_fp8xfp4_tflops"]), 4)
+        out["measured_ceilings"] = ceil
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.workload, args.M)
     print(json.dumps(out), flush=True)

@@ -170,6 +170,29 @@ int zqfp_w4a8_gemm_lorc(const uint8_t *Xq, const float *sx, int64_t M, int64_t K
                         void *Y, int64_t ldy, int out_dtype, int accum,
                         void *workspace, void *stream);
 
+/*
+ * Measurement probes (no part of the paper's method): what the device itself
+ * sustains, for reporting roofline fractions against measured ceilings next to
+ * the published peaks.  Both only enqueue work on `stream`; the caller times it.
+ *
+ * zqfp_probe_stream_read -- a plain streaming read of `bytes` bytes at `src`
+ *   (device, 16-byte aligned; the last bytes % (workgroups * 32 KB) are not
+ *   read).  sink: device, >= 4 * workgroups bytes, written at most once per
+ *   workgroup with a value that means nothing.
+ * zqfp_probe_mfma -- `iters` rounds of 32 independent
+ *   v_mfma_scale_f32_16x16x128_f8f6f4 instructions (FP8 x FP4) per wave, 8 waves
+ *   per workgroup, operands held in registers: 2 * 16*16*128 * 32 * 8 * iters *
+ *   workgroups floating-point operations in total.  operands: device, 4096
+ *   bytes of anything; sink: device, >= 2048 * workgroups bytes.
+ *
+ * Return ZQFP_OK, ZQFP_E_NULL, ZQFP_E_SHAPE (non-positive sizes), ZQFP_E_ALIGN
+ * or ZQFP_E_HIP.
+ */
+int zqfp_probe_stream_read(const void *src, int64_t bytes, void *sink,
+                           int workgroups, void *stream);
+int zqfp_probe_mfma(const void *operands, void *sink, int iters,
+                    int workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

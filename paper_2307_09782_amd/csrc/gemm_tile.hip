@@ -535,10 +535,13 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
                        void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
     // 256 x 256 tiles (8 waves, one workgroup per compute unit) once they fill the 256 compute units
-    // at least ~1.5 times; else 128 x 128 (4 waves, two workgroups per compute unit) under the same
-    // condition; else 64 x 128, which also serves 16 < M <= 64, where the kernel is a weight stream.
+    // at least ~1.5 times, or fill three quarters of them in a single round; else 128 x 128 (4 waves,
+    // two workgroups per compute unit) if there are enough of those; else 64 x 128, which also serves
+    // 16 < M <= 64, where the kernel is a weight stream.
+    constexpr int64_t kCUs = 256;  // MI355X
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.Np + bn - 1) / bn); };
-    if (tiles(256, 256) >= 384) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    const int64_t n256 = tiles(256, 256);
+    if (n256 >= kCUs * 3 / 2 || (n256 <= kCUs && n256 * 4 >= kCUs * 3)) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
     if (M > 64 && tiles(128, 128) >= 384) return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
     return launch_cfg<2, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
 }

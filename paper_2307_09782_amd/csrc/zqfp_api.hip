@@ -115,4 +115,23 @@ int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K
     return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, stream);
 }
 
+int zqfp_probe_stream_read(const void* src, int64_t bytes, void* sink, int workgroups, void* stream)
+{
+    if (bytes <= 0 || workgroups <= 0) return ZQFP_E_SHAPE;
+    if (!src || !sink) return ZQFP_E_NULL;
+    if (!aligned16(src)) return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_probe_read(src, bytes, static_cast<uint32_t*>(sink), workgroups,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_probe_mfma(const void* operands, void* sink, int iters, int workgroups, void* stream)
+{
+    if (iters <= 0 || workgroups <= 0) return ZQFP_E_SHAPE;
+    if (!operands || !sink) return ZQFP_E_NULL;
+    hipError_t e = zqfp::launch_probe_mfma(static_cast<const uint32_t*>(operands), static_cast<float*>(sink), iters,
+                                           workgroups, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -127,5 +127,7 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                               int accum, hipStream_t s);
 bool gemm_decode_supported(int64_t M, const BlobLayout& L);
+hipError_t launch_probe_read(const void* src, int64_t bytes, uint32_t* sink, int workgroups, hipStream_t s);
+hipError_t launch_probe_mfma(const uint32_t* operands, float* sink, int iters, int workgroups, hipStream_t s);
 
 }  // namespace zqfp

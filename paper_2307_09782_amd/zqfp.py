@@ -55,6 +55,10 @@ def lib():
         L.zqfp_w4a8_gemm.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, i64, c.c_int, c.c_int, p, p]
         L.zqfp_w4a8_gemm_lorc.restype = c.c_int
         L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_probe_stream_read.restype = c.c_int
+        L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
+        L.zqfp_probe_mfma.restype = c.c_int
+        L.zqfp_probe_mfma.argtypes = [p, p, c.c_int, c.c_int, p]
         _lib = L
     return _lib
 
@@ -155,3 +159,21 @@ def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=AC
     _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
                                      Y.stride(0), code, accum, _ptr(ws), _stream(Xq)))
     return Y
+
+
+def probe_stream_read(src, sink, workgroups):
+    """Enqueue a plain streaming read of the uint8 tensor `src` (measurement probe; the caller times it)."""
+    _dev(src, torch.uint8, 1), _dev(sink, torch.int32, 1)
+    if sink.numel() < workgroups:
+        raise ZqfpError(-2, "sink smaller than the workgroup count")
+    _check(lib().zqfp_probe_stream_read(_ptr(src), src.numel(), _ptr(sink), workgroups, _stream(src)))
+
+
+def probe_mfma(operands, sink, iters, workgroups):
+    """Enqueue `iters` rounds of 32 FP8 x FP4 matrix instructions per wave on `workgroups` workgroups of 8
+    waves (measurement probe; the caller times it).  Returns the floating-point operations enqueued."""
+    _dev(operands, torch.int32, 1), _dev(sink, torch.float32, 1)
+    if operands.numel() < 1024 or sink.numel() < 512 * workgroups:
+        raise ZqfpError(-2, "probe buffers too small")
+    _check(lib().zqfp_probe_mfma(_ptr(operands), _ptr(sink), iters, workgroups, _stream(operands)))
+    return 2.0 * 16 * 16 * 128 * 32 * 8 * iters * workgroups

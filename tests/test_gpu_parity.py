@@ -278,3 +278,25 @@ def test_fast_mode_meets_its_documented_bound(M, K, N, seed_cfg):
     ratio = (err / Sabs).max()
     print(f"fast: rel-Fro {fro:.2e} ratio {ratio:.2e} (2^-18 = {2.0**-18:.2e})")
     assert fro <= 1e-4 and ratio <= 2.0 ** -10
+
+
+@pytest.mark.gpu
+def test_measurement_probes_run_and_report_sane_rates():
+    """The two probes behind bench.py's measured ceilings: they must run, leave their inputs
+    untouched and land between loose physical bounds (not a parity check: no method arithmetic)."""
+    src = torch.full((1 << 28,), 7, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    ops = torch.arange(1024, dtype=torch.int32, device="cuda")
+    fsink = torch.zeros(512 * 64, dtype=torch.float32, device="cuda")
+    zqfp.probe_stream_read(src, sink, 1024)
+    flop = zqfp.probe_mfma(ops, fsink, 10, 64)
+    torch.cuda.synchronize()
+    assert flop == 2.0 * 16 * 16 * 128 * 32 * 8 * 10 * 64
+    assert int(src[:4096].sum().item()) == 7 * 4096 and int(ops[5].item()) == 5
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    zqfp.probe_stream_read(src, sink, 1024)
+    b.record()
+    torch.cuda.synchronize()
+    gbs = src.numel() / (a.elapsed_time(b) * 1e-3) / 1e9
+    assert 500.0 < gbs < 20000.0, gbs
