@@ -194,6 +194,11 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (7, 512, 48, 128, 2, 16),       # decode form, rank too large for registers: read in place
     (16, 8192, 80, 128, 1, 8),      # decode form, 64 k-tiles (8 per wave) with LoRC
     (3, 5120, 96, 128, 2, 5),       # decode form, 40 k-tiles (5 per wave)
+    (17, 384, 72, 128, 1, 0),       # smallest M of the tiled form (64 x 128 tiles), N not a multiple of 16
+    (64, 2048, 200, 256, 2, 8),     # 64 x 128 tiles, 16 k-steps, groups of 256, LoRC staged in LDS
+    (48, 128, 64, 32, 1, 2),        # a single k-step (no load pipeline to speak of), groups of 32
+    (130, 256, 300, 64, 2, 0),      # two k-steps, groups of 64
+    (20, 8320, 48, 128, 1, 0),      # N < 64: streaming fallback
 ])
 def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
