@@ -221,7 +221,7 @@ def measured_ceilings():
             "mfma_fp8xfp4_tflops": round(flop[0] / (ms_mfma * 1e-3) / 1e12, 1)}
 
 
-def cpu_baseline(name, M, rows=2048):
+def cpu_baseline(name, M, rows=4096):
     """The CPU oracle on a bounded sample: `rows` tokens of the same workload,
     whole hot path (quantize, LoRC left factor, GEMM over all N)."""
     import oracle

@@ -69,6 +69,8 @@ def lib():
                                        p, p, c.c_int, p, p, c.c_int64, p, p]
         L.orc_lorc_left.restype = None
         L.orc_lorc_left.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int, p, p]
+        L.orc_rmsnorm_bf16.restype = None
+        L.orc_rmsnorm_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_float, p]
         L.orc_max_threads.restype = c.c_int
         L.orc_max_threads.argtypes = []
         _lib = L
@@ -123,6 +125,17 @@ def quantize_act(X):
     sx = np.empty((M,), np.float32)
     lib().orc_quantize_act(_ptr(X), M, K, K, _ptr(Xq), _ptr(sx))
     return Xq, sx
+
+
+def rmsnorm_bf16(X, g, eps):
+    """RMS normalisation of bf16 rows (bits) with bf16 gain g, result rounded to bf16 (bits)."""
+    _chk(X, np.uint16, 2), _chk(g, np.uint16, 1)
+    M, K = X.shape
+    if g.shape[0] != K or not eps > 0:
+        raise ValueError("gain length / eps")
+    Y = np.empty((M, K), np.uint16)
+    lib().orc_rmsnorm_bf16(_ptr(X), M, K, K, _ptr(g), float(eps), _ptr(Y))
+    return Y
 
 
 def pack_weight(W, G, mode):

@@ -20,6 +20,8 @@
  *   gemm         : the W4A8 linear layer the cast exists for (Sections 1, 3):
  *                  Y = Q8(X) . Q4(W), written out as the plain definition with
  *                  an fp64 sum.
+ *   rmsnorm      : the normalisation whose output Section 3 quantizes (textbook
+ *                  definition; see orc_rmsnorm_bf16).
  *   lorc         : Section 3 (LoRC: the low-rank product U.V is added to the
  *                  quantized weight), Appendix A (rank 8 for LLaMA).
  *
@@ -219,6 +221,54 @@ void orc_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
         for (int64_t k = 0; k < K; ++k) {
             volatile float y = bf16_bits_to_f32(row[k]) * inv; /* one binary32 product */
             Xq[m * K + k] = orc_e4m3_encode(y);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* RMS normalisation feeding the quantizer                             */
+/* ------------------------------------------------------------------ */
+
+/* binary32 -> bfloat16 bits, round to nearest even (finite inputs) */
+static uint16_t f32_to_bf16_bits_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/* The activations the paper quantizes token-wise are outputs of a normalisation
+ * layer (Section 3, "Distribution of Activations": the inputs of attn.q_proj and
+ * fc1 "have undergone layer-normalization"); for the LLaMA models of Section 4
+ * that layer is RMSNorm.  This is its textbook definition,
+ *     y[k] = x[k] / sqrt(mean_k(x[k]^2) + eps) * g[k],
+ * with the result rounded to bfloat16, i.e. what a stand-alone normalisation
+ * kernel would hand to orc_quantize_act.  Fixed arithmetic so that the codes
+ * downstream have one right answer: the sum of squares in binary64 (every
+ * square of a bfloat16 is exact there), then binary32 steps
+ *     ms = fl32(ss / K); t = ms + eps; s = sqrt(t); rstd = 1 / s;
+ *     y = bf16_rne( (x * rstd) * g ).
+ * eps must be positive (an all-zero row then gives zeros).
+ * X: M x K bf16 bits, row stride ldx.  g: K bf16 bits.  Y: M x K bf16 bits, dense. */
+void orc_rmsnorm_bf16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                      const uint16_t *g, float eps, uint16_t *Y)
+{
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *row = X + m * ldx;
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double x = (double)bf16_bits_to_f32(row[k]);
+            ss += x * x;
+        }
+        volatile float ms = (float)(ss / (double)K);
+        volatile float t = ms + eps;
+        volatile float s = sqrtf(t);
+        volatile float rstd = 1.0f / s;
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float a = bf16_bits_to_f32(row[k]) * rstd;
+            volatile float b = a * bf16_bits_to_f32(g[k]);
+            Y[m * K + k] = f32_to_bf16_bits_rne(b);
         }
     }
 }
