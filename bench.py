@@ -186,6 +186,40 @@ def calibration_copy(nbytes=1 << 30):
     torch.cuda.empty_cache()
 
 
+def quantizer_rows(name="llama7b_qkv", M=4096):
+    """The quantizer alone and fused behind RMS normalisation, HBM-bound (2 B read + 1 B written per
+    element): one HIP graph of calls rotating through input copies that exceed the last-level cache."""
+    cfg = inputs.CONFIGS[name]
+    X = bf16_dev(inputs.make_x(cfg, M))
+    copies = max(1, -(-600_000_000 // (2 * M * cfg.K)))
+    Xs = [X] + [X.clone() for _ in range(copies - 1)]
+    gain = torch.ones(cfg.K, dtype=torch.bfloat16, device="cuda")
+    rows = []
+    for label, fn in (("quantize_act_fp8", lambda x: zqfp.quantize_act_fp8(x)),
+                      ("rmsnorm_quantize_act_fp8", lambda x: zqfp.rmsnorm_quantize_act_fp8(x, gain, 1e-5))):
+        for x in Xs[:2]:
+            fn(x)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for x in Xs:
+                fn(x)
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / (5 * len(Xs))
+        nbytes = 3 * M * cfg.K + 4 * M + (2 * cfg.K if label.startswith("rms") else 0)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        rows.append({"call": label, "workload": f"{M}x{cfg.K} bf16", "ms": round(ms, 5), "gbs": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "input_copies_rotated": len(Xs)})
+    return rows
+
+
 def measured_ceilings():
     """What the device itself sustains right now (measurement probes of the library, timed with HIP
     events): a plain streaming read of 2 GiB, twice the last-level cache eight times over, and a
@@ -320,6 +354,7 @@ def main():
         out["also"] = also
 
     if not args.no_also:
+        out["quantizer"] = quantizer_rows()
         ceil = measured_ceilings()
         rf = out["roofline"]
         ceil["frac_of_measured"] = round(rf["achieved"] / (ceil["stream_read_gbs"] if rf["bound"] == "hbm" else ceil["mfma_fp8xfp4_tflops"]), 4)

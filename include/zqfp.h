@@ -99,6 +99,30 @@ int zqfp_quantize_act_fp8(const void *X, int64_t M, int64_t K, int64_t ldx,
                           void *stream);
 
 /*
+ * rmsnorm_quantize_act_fp8 -- the same quantizer fused behind the RMS
+ * normalisation that produces the activations (paper Section 3, "Distribution
+ * of Activations": the quantized inputs of attn.q_proj and fc1 are outputs of
+ * a normalisation layer; RMSNorm for the LLaMA models of Section 4):
+ *
+ *   y[m,k] = bf16( X[m,k] / sqrt(mean_k X[m,k]^2 + eps) * gain[k] )
+ *
+ * followed by zqfp_quantize_act_fp8 applied to y, without y ever leaving the
+ * registers.  Sum of squares in binary64; then, in IEEE binary32,
+ * ms = fl(ss / K), rstd = 1 / sqrt(ms + eps), y = bf16_rne((x * rstd) * gain).
+ * The codes and scales are those of the unfused sequence, bit for bit.
+ *
+ *   gain  [K] bfloat16 (device, 16-byte aligned)                      (in)
+ *   eps   > 0
+ *   K     <= 32768 (a token's row is held in registers)
+ *   T     = y . U when U != NULL (the LoRC branch sees the normalised y)
+ * Other arguments and errors as for zqfp_quantize_act_fp8.
+ */
+int zqfp_rmsnorm_quantize_act_fp8(const void *X, const void *gain, float eps,
+                                  int64_t M, int64_t K, int64_t ldx,
+                                  uint8_t *Xq, float *sx,
+                                  const void *U, int r, float *T, void *stream);
+
+/*
  * pack_weight_fp4 -- group-wise FP4 (E2M1) weight quantization with
  * power-of-two scales (paper Section 3: fine-grained quantization; "Casting
  * the FP4 to FP8": S = 2^n with methods M1 / M2; Appendix A: group size).

@@ -87,10 +87,43 @@ __device__ inline void lorc_accumulate(float (&acc)[RP], const float (&x)[8], co
 
 // NT threads per token: 256 when there are tokens enough to fill the chip, 1024 for a handful of
 // tokens (decode), where one row's latency chain is all there is.
-template <int RP, int NT>
+__device__ inline uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
+    return u >> 16;
+}
+
+// 8 bf16 -> 8 bf16: (x * rstd) * g, each product one binary32 operation, rounded to bf16
+__device__ inline uint4 normalize8(uint4 v, uint4 g, float rstd)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {g.x, g.y, g.z, g.w}, o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = (bf16_lo(w[i]) * rstd) * bf16_lo(gw[i]);
+        const float hi = (bf16_hi(w[i]) * rstd) * bf16_hi(gw[i]);
+        o[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ inline double sum_squares(double acc, uint4 v)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const double lo = (double)bf16_lo(w[i]), hi = (double)bf16_hi(w[i]);
+        acc += lo * lo;  // each square is exact in binary64
+        acc += hi * hi;
+    }
+    return acc;
+}
+
+template <int RP, int NT, bool NORM>
 __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict__ X, int64_t K, int64_t ldx,
                                                          uint8_t* __restrict__ Xq, float* __restrict__ sx,
-                                                         const uint16_t* __restrict__ U, int r, float* __restrict__ T)
+                                                         const uint16_t* __restrict__ U, int r, float* __restrict__ T,
+                                                         const uint16_t* __restrict__ gain, float eps)
 {
     constexpr int kThreads = NT, kWaves = NT / 64;
     __shared__ uint32_t s_amax[kWaves];
@@ -103,15 +136,44 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
     const int nchunk = (int)(K / 8);
 
     uint4 v[kRegChunks];
-    uint32_t am = 0;
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         int idx = tid + c * kThreads;
         v[c] = make_uint4(0, 0, 0, 0);
         if (idx < nchunk) v[c] = xrow[idx];
-        am = absmax_bits(am, v[c]);
     }
-    for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) am = absmax_bits(am, xrow[idx]);
+    if constexpr (NORM) {
+        // the whole row sits in registers (the launcher guarantees K <= 8 * kRegChunks * NT): sum of
+        // squares in binary64, waves meet in LDS and every thread adds the partial sums in the same
+        // order; then the normalised row replaces the row
+        __shared__ double s_ss[kWaves];
+        const uint4* grow = reinterpret_cast<const uint4*>(gain);
+        uint4 g[kRegChunks];
+        double ss = 0.0;
+#pragma unroll
+        for (int c = 0; c < kRegChunks; ++c) {
+            int idx = tid + c * kThreads;
+            g[c] = make_uint4(0, 0, 0, 0);
+            if (idx < nchunk) g[c] = grow[idx];
+            ss = sum_squares(ss, v[c]);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+        if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
+        __syncthreads();
+        ss = s_ss[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) ss += s_ss[w];
+        const float ms = (float)(ss / (double)K);
+        const float rstd = 1.0f / sqrtf(ms + eps);  // IEEE binary32 add, square root, division
+#pragma unroll
+        for (int c = 0; c < kRegChunks; ++c) v[c] = normalize8(v[c], g[c], rstd);
+    }
+    uint32_t am = 0;
+#pragma unroll
+    for (int c = 0; c < kRegChunks; ++c) am = absmax_bits(am, v[c]);
+    if constexpr (!NORM)
+        for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) am = absmax_bits(am, xrow[idx]);
 
     // LoRC left factor first: its loads of U overlap the row's own loads and the absmax reduction.
     // A lane holds 8 consecutive elements; for the product with U it trades them, through a
@@ -133,8 +195,9 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
             int idx = tid + c * kThreads;
             if (idx - lane < nchunk) one_chunk(idx < nchunk ? v[c] : make_uint4(0, 0, 0, 0), idx);
         }
-        for (int idx = tid + kRegChunks * kThreads; idx - lane < nchunk; idx += kThreads)
-            one_chunk(idx < nchunk ? xrow[idx] : make_uint4(0, 0, 0, 0), idx);
+        if constexpr (!NORM)
+            for (int idx = tid + kRegChunks * kThreads; idx - lane < nchunk; idx += kThreads)
+                one_chunk(idx < nchunk ? xrow[idx] : make_uint4(0, 0, 0, 0), idx);
     }
 
 #pragma unroll
@@ -158,7 +221,8 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
         int idx = tid + c * kThreads;
         if (idx < nchunk) qrow[idx] = encode8(v[c], inv);
     }
-    for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) qrow[idx] = encode8(xrow[idx], inv);
+    if constexpr (!NORM)
+        for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) qrow[idx] = encode8(xrow[idx], inv);
 
     if constexpr (RP > 0) {
 #pragma unroll
@@ -178,17 +242,94 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
     }
 }
 
+// ---------------------------------------------------------------------------
+// Wave-per-token form for many tokens without the LoRC factor: a row of up to 8 * 64 * MAXC
+// elements sits in one wave's registers (16 B per lane per load, 1 KB contiguous per instruction),
+// the reductions are wave shuffles only, and no barrier or LDS is involved; 16 waves per compute
+// unit keep 8 * MAXC KB of loads in flight each.
+// ---------------------------------------------------------------------------
+template <int MAXC, bool NORM>
+__global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
+                                                     uint8_t* __restrict__ Xq, float* __restrict__ sx,
+                                                     const uint16_t* __restrict__ gain, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;  // whole waves leave; nothing below synchronises across waves
+    const uint4* xrow = reinterpret_cast<const uint4*>(X + row * ldx);
+    uint2* qrow = reinterpret_cast<uint2*>(Xq + row * K);
+    const int nchunk = (int)(K / 8);
+
+    uint4 v[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int idx = c * 64 + lane;
+        v[c] = make_uint4(0, 0, 0, 0);
+        if (idx < nchunk) v[c] = xrow[idx];
+    }
+    if constexpr (NORM) {
+        double ss = 0.0;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) ss = sum_squares(ss, v[c]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);  // every lane ends with the same sum
+        const float ms = (float)(ss / (double)K);
+        const float rstd = 1.0f / sqrtf(ms + eps);  // IEEE binary32 add, square root, division
+        const uint4* grow = reinterpret_cast<const uint4*>(gain);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int idx = c * 64 + lane;
+            if (idx < nchunk) v[c] = normalize8(v[c], grow[idx], rstd);
+        }
+    }
+    uint32_t am = 0;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) am = absmax_bits(am, v[c]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) am = max(am, (uint32_t)__shfl_xor((int)am, off));
+    const float amax = __uint_as_float(am << 16);
+    float scale = 1.0f, inv = 0.0f;  // all-zero (or vanishing) token: signed-zero codes, scale 1
+    if (amax >= 0x1p-96f) {
+        scale = amax / 448.0f;  // IEEE binary32 division
+        inv = 448.0f / amax;    // IEEE binary32 division
+    }
+    if (lane == 0) sx[row] = scale;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int idx = c * 64 + lane;
+        if (idx < nchunk) qrow[idx] = encode8(v[c], inv);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx,
-                               const uint16_t* U, int r, float* T, hipStream_t s)
+                               const uint16_t* U, int r, float* T, const uint16_t* gain, float eps, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
+    const bool norm = gain != nullptr;
+    if (r == 0 && M >= 1024 && K <= 8192) {  // many tokens, no LoRC factor: one wave per token
+        const dim3 g4((unsigned)((M + 3) / 4));
+#define ZQ_ROWS(MAXC)                                                                                                  \
+    do {                                                                                                               \
+        if (norm) hipLaunchKernelGGL((k_quantize_rows<MAXC, true>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, eps);  \
+        else hipLaunchKernelGGL((k_quantize_rows<MAXC, false>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, eps);      \
+    } while (0)
+        if (K <= 2048) ZQ_ROWS(4);
+        else if (K <= 4096) ZQ_ROWS(8);
+        else ZQ_ROWS(16);
+#undef ZQ_ROWS
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)M);
-#define ZQ_QUANT(RP)                                                                                           \
-    do {                                                                                                       \
-        if (M <= 64 && K >= 2048) hipLaunchKernelGGL((k_quantize_act<RP, 1024>), grid, dim3(1024), 0, s, X, K, ldx, Xq, sx, U, r, T); \
-        else hipLaunchKernelGGL((k_quantize_act<RP, 256>), grid, dim3(256), 0, s, X, K, ldx, Xq, sx, U, r, T);   \
+    // 1024 threads per token for a handful of tokens, and for normalised rows too long for 256 threads' registers
+    const bool wide = (M <= 64 && K >= 2048) || (norm && K > 8 * kRegChunks * 256);
+#define ZQ_QUANT(RP)                                                                                                       \
+    do {                                                                                                                   \
+        if (norm && wide) hipLaunchKernelGGL((k_quantize_act<RP, 1024, true>), grid, dim3(1024), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps); \
+        else if (norm) hipLaunchKernelGGL((k_quantize_act<RP, 256, true>), grid, dim3(256), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);      \
+        else if (wide) hipLaunchKernelGGL((k_quantize_act<RP, 1024, false>), grid, dim3(1024), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);   \
+        else hipLaunchKernelGGL((k_quantize_act<RP, 256, false>), grid, dim3(256), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);               \
     } while (0)
     if (r == 0) ZQ_QUANT(0);
     else if (r <= 8) ZQ_QUANT(8);

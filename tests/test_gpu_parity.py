@@ -22,7 +22,9 @@ def _sync_np(t):
 
 # ------------------------------------------------------------------ quantizer
 @pytest.mark.parametrize("name,M", [("tiny", 16), ("opt1p3b_fc1", 300), ("llama7b_qkv", 1), ("llama7b_qkv", 77),
-                                    ("llama13b_ffn_lorc", 16), ("llama70b_ffn_decode", 64)])
+                                    ("llama13b_ffn_lorc", 16), ("llama70b_ffn_decode", 64),
+                                    # the wave-per-token kernel, with a ragged last workgroup
+                                    ("opt1p3b_fc1", 1027), ("llama7b_qkv", 1100), ("llama70b_ffn_decode", 1025)])
 def test_quantizer_codes_and_scales_bit_exact(name, M):
     cfg = CFG[name]
     X = inputs.make_x(cfg, M)
@@ -305,3 +307,49 @@ def test_measurement_probes_run_and_report_sane_rates():
     torch.cuda.synchronize()
     gbs = src.numel() / (a.elapsed_time(b) * 1e-3) / 1e9
     assert 500.0 < gbs < 20000.0, gbs
+
+
+def _gain_bits(K, seed=3):
+    rng = np.random.default_rng(seed)
+    return inputs.f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,M,eps", [("tiny", 16, 1e-5), ("opt1p3b_fc1", 300, 1e-5), ("llama7b_qkv", 77, 1e-6),
+                                        ("llama13b_ffn_lorc", 16, 1e-5), ("llama70b_ffn_decode", 64, 1e-5),
+                                        ("llama70b_ffn_decode", 130, 1e-2),
+                                        # many tokens without LoRC: the wave-per-token kernel (K = 2048, 4096, 8192)
+                                        ("opt1p3b_fc1", 1027, 1e-5), ("llama7b_qkv", 1100, 1e-5)])
+def test_fused_rmsnorm_quantizer_equals_the_unfused_sequence_bit_for_bit(name, M, eps):
+    """RMS normalisation fused in front of the quantizer: codes and scales are those of the oracle's
+    normalisation (bf16 result) followed by the oracle's quantizer; the LoRC left factor is taken from
+    the normalised rows."""
+    cfg = CFG[name]
+    X = inputs.make_x(cfg, M)
+    X[M // 2] = 0  # an all-zero token
+    g = _gain_bits(cfg.K)
+    Yn = oracle.rmsnorm_bf16(X, g, eps)
+    Xq_o, sx_o = oracle.quantize_act(Yn)
+    gd = bf16_tensor(g.reshape(1, -1)).reshape(-1).contiguous()
+    if cfg.rank:
+        U, _ = inputs.make_uv(cfg)
+        T_o, Tabs = oracle.lorc_left(Yn, U)
+        Xq, sx, T = zqfp.rmsnorm_quantize_act_fp8(bf16_tensor(X), gd, eps, f16_tensor(U))
+        T = _sync_np(T)
+        assert np.all(np.abs(T - T_o) <= 2.0 ** -18 * Tabs + 1e-30)
+    else:
+        Xq, sx = zqfp.rmsnorm_quantize_act_fp8(bf16_tensor(X), gd, eps)
+    Xq, sx = _sync_np(Xq), _sync_np(sx)
+    assert bits_equal_f32(sx, sx_o)
+    assert np.array_equal(Xq, Xq_o)
+    assert np.all(Xq[M // 2] == 0) and sx[M // 2] == 1.0
+
+
+@pytest.mark.gpu
+def test_fused_rmsnorm_quantizer_argument_checks():
+    X = bf16_tensor(inputs.make_x(CFG["tiny"], 4))
+    g = bf16_tensor(_gain_bits(256).reshape(1, -1)).reshape(-1).contiguous()
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.rmsnorm_quantize_act_fp8(X, g, 0.0)
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.rmsnorm_quantize_act_fp8(X, g[:128].contiguous(), 1e-5)
