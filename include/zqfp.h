@@ -170,8 +170,12 @@ int zqfp_unpack_codes(const void *packed, int64_t K, int64_t N, int G,
  *   Xq, sx   as produced by zqfp_quantize_act_fp8                     (in)
  *   packed   as produced by zqfp_pack_weight_fp4 for (K, N, G)         (in)
  *   Y        [M, N], row stride ldy elements, float32 or bfloat16     (out)
- *   workspace  zqfp_gemm_workspace_bytes(M, K, N) bytes (may be NULL if that
- *            is 0); contents need not be initialised and are not preserved.
+ *   workspace  zqfp_gemm_workspace_bytes(M, K, N) bytes of device memory,
+ *            16-byte aligned; contents need not be initialised and are not
+ *            preserved.  It is non-zero only where few output tiles meet a long
+ *            K (K is then cut into slices whose float32 partial tiles are summed
+ *            in fixed order by a second kernel).  NULL is always accepted: the
+ *            call then runs without the split (same result within tolerance).
  */
 size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int zqfp_w4a8_gemm(const uint8_t *Xq, const float *sx, int64_t M, int64_t K,

@@ -118,7 +118,8 @@ struct TileCfg {
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
-    BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n)
+    BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n, int ksplit,
+    int kslice, float* __restrict__ partial)
 {
     using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
     constexpr int kThreads = C::THREADS;
@@ -127,14 +128,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // ---- workgroup -> tile.  Consecutive workgroup ids go to consecutive XCDs (8 of them, one
     // L2 each), so give every XCD a contiguous range of tiles, walked in column-panels of height 8
     // so that concurrently running workgroups of an XCD share activation and weight panels in L2.
+    // With a K-split every tile appears ksplit times, once per slice of kslice k-tiles.
     const int ntiles = tiles_m * tiles_n;
-    int pid = blockIdx.x;
+    int pid = blockIdx.x, slice = 0;
     {
-        const int per = (ntiles + 7) / 8;
+        const int units = ntiles * ksplit;
+        const int per = (units + 7) / 8;
         const int xcd = pid & 7, loc = pid >> 3;
         const int id = xcd * per + loc;
-        if (id >= ntiles) return;
-        pid = id;
+        if (id >= units) return;
+        pid = id / ksplit;
+        slice = id - pid * ksplit;
     }
     constexpr int GROUP_M = 8;
     const int in_group = GROUP_M * tiles_n;
@@ -150,7 +154,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     const int col = lane & 15, lb = lane >> 4;
     const int64_t m0 = (int64_t)tm * C::BM;
     const int64_t strip0 = (int64_t)tn * (C::BN / 16);
-    const int nkt = (int)L.nkt;
+    const int nkt_all = (int)L.nkt;                 // k-tiles of the whole K (the packed layout's stride)
+    const int kt0 = slice * kslice;                 // this workgroup's first k-tile
+    const int nkt = min(kslice, nkt_all - kt0);     // and how many it multiplies (>= 1)
 
     // ---- load addresses: uniform base pointers plus 32-bit per-lane offsets.  Rows past M
     // and strips past the last one are clamped to the last valid one: what they produce is
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     for (int i = 0; i < C::B_CHUNKS; ++i) {
         const int cidx = tid + kThreads * i;
         const int64_t strip = min(strip0 + (cidx >> 6), L.nstrips - 1);
-        b_off[i] = (uint32_t)((strip * nkt * 64 + (cidx & 63)) * 16);
+        b_off[i] = (uint32_t)((strip * nkt_all * 64 + (cidx & 63)) * 16);
     }
     // exponent dwords, [strip][quad][column] in memory: thread t stages the dword of column
     // t % BN of the tile; it lands in LDS as [column] and every lane later picks its own.
@@ -208,11 +214,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // t-th load of k-tile kt into LDS stage `stage`
     auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) __attribute__((always_inline)) {
         const uint32_t st = (uint32_t)stage * C::STAGE;
-        if (t < C::A_CHUNKS) lds_load16(a_base + kt * 128, a_off[t], st + a_dst + t * (kThreads / 64) * 1024);
+        if (t < C::A_CHUNKS) lds_load16(a_base + (kt0 + kt) * 128, a_off[t], st + a_dst + t * (kThreads / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            lds_load16(b_base + (int64_t)kt * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kThreads / 64) * 1024);
+            lds_load16(b_base + (int64_t)(kt0 + kt) * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kThreads / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
-            lds_load4(e_base + (group_of(c, kt, 0) >> 2) * 64, e_off, st + e_dst);
+            lds_load4(e_base + (group_of(c, kt0 + kt, 0) >> 2) * 64, e_off, st + e_dst);
     };
 
     v4f acc[WTM][WTN];
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     uint32_t e_cur[WTN];  // their exponent dwords (raw until the first use in a step)
     v8i fx, fy, fz;
     u32x4 ta, tb;         // the activation fragment in flight
-    GroupCursor cur_comp = {0, 0}, cur_load = {0, 0};
+    GroupCursor cur_comp = {kt0 / gq, kt0 % gq}, cur_load = cur_comp;  // at this workgroup's first k-tile
     // per-lane LDS addresses inside stage 0 (the stage offset is added per step)
     const uint32_t a_addr0 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7)) * 16);
     const uint32_t a_addr1 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
@@ -271,7 +277,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         constexpr bool fetch = !last_block || NEXT;
         v8i& cur = (I & 1) ? fz : fy;
         v8i& inc = (I & 1) ? fy : fz;
-        const int esh = 8 * (group_of(cur_comp, kt, lb) & 3);  // this lane's exponent byte: (stored group & 3) of the dword
+        const int esh = 8 * (group_of(cur_comp, kt0 + kt, lb) & 3);  // this lane's exponent byte: (stored group & 3) of the dword
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, PASSES>([&](auto p_tag) __attribute__((always_inline)) {
             constexpr int P = decltype(p_tag)::value;
@@ -411,9 +417,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     float* patch = reinterpret_cast<float*>(smem) + wave * (16 * SLAB_LD);
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
     const int64_t n_wave = (strip0 + wn * WTN) * 16;
+    // With a K-split the workgroup hands its raw float32 sums to slice `slice` of the workspace
+    // ([ksplit][M][Np]); scales and LoRC are applied by the kernel that adds the slices up.
+    const bool raw = ksplit > 1;
+    if (raw) {
+        Y = partial + (int64_t)slice * M * L.Np;
+        ldy = L.Np;
+        out_dtype = 0;
+    }
     float cn[WTN];
 #pragma unroll
-    for (int j = 0; j < WTN; ++j) cn[j] = colscale[min(n_wave + j * 16 + col, L.Np - 1)];
+    for (int j = 0; j < WTN; ++j) cn[j] = raw ? 1.0f : colscale[min(n_wave + j * 16 + col, L.Np - 1)];
     // LoRC of rank <= 8 (the paper's setting): the tile's rows of T and columns of V go through LDS
     // once (zero-padded to rank 8, V converted to binary32), so that the 8 fused multiply-adds per
     // output read registers filled by two 16-byte LDS reads per row and per column.
@@ -422,7 +436,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     static_assert(PATCH_BYTES + (C::BM + C::BN) * RL * 4 <= C::NSTAGE * C::STAGE, "LoRC tiles do not fit the stages");
     float* Ts = reinterpret_cast<float*>(smem + PATCH_BYTES);  // [BM][RL]
     float* Vs = Ts + C::BM * RL;                               // [BN][RL]
-    const int rk = lorc.r;
+    const int rk = raw ? 0 : lorc.r;
     const bool lorc_lds = rk > 0 && rk <= RL;
     if (lorc_lds) {
         for (int idx = tid; idx < C::BM * RL; idx += kThreads) {
@@ -445,7 +459,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         const int64_t m_slab = m0 + (wm * WTM + i) * 16;
         float sxm[4];
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) sxm[rg] = sx[min(m_slab + 4 * lb + rg, M - 1)];
+        for (int rg = 0; rg < 4; ++rg) sxm[rg] = raw ? 1.0f : sx[min(m_slab + 4 * lb + rg, M - 1)];
         v4f tl[4][RL / 4];
         if (lorc_lds) {
 #pragma unroll
@@ -508,14 +522,40 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     }
 }
 
+// Sums the K slices of a split launch in slice order and applies what the tile epilogue would have:
+// Y[m,n] = (sx[m] c[n]) * sum_s partial[s][m][n] (+ T.V).  Four consecutive columns per thread.
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ partial, int ksplit, int64_t M,
+                                                     const uint8_t* __restrict__ blob, BlobLayout L,
+                                                     const float* __restrict__ sx, Lorc lorc, void* __restrict__ Y,
+                                                     int64_t ldy, int out_dtype)
+{
+    const int64_t quads = L.Np / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * quads) return;
+    const int64_t m = idx / quads, n0 = (idx - m * quads) * 4;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < ksplit; ++s) acc += *reinterpret_cast<const v4f*>(partial + ((int64_t)s * M + m) * L.Np + n0);
+    const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
+    const float sm = sx[m];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t n = n0 + q;
+        if (n >= L.N) break;
+        float y = (sm * colscale[n]) * acc[q];
+        for (int j = 0; j < lorc.r; ++j) y = fmaf(lorc.T[m * lorc.r + j], half_bits_to_f32(lorc.V[(int64_t)j * L.N + n]), y);
+        if (out_dtype == 0) reinterpret_cast<float*>(Y)[m * ldy + n] = y;
+        else reinterpret_cast<uint16_t*>(Y)[m * ldy + n] = f32_to_bf16_bits(y);
+    }
+}
+
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
-                      void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+                      void* Y, int64_t ldy, int out_dtype, int ksplit, int kslice, float* partial, hipStream_t s)
 {
     using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
-    const int ntiles = tiles_m * tiles_n;
-    const int per = (ntiles + 7) / 8;
+    const int units = tiles_m * tiles_n * ksplit;
+    const int per = (units + 7) / 8;
     const size_t smem = C::NSTAGE * C::STAGE;
     auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, EXACT>;
     static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
@@ -526,24 +566,25 @@ hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(C::THREADS), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy,
-                       out_dtype, tiles_m, tiles_n);
+                       out_dtype, tiles_m, tiles_n, ksplit, kslice, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || ksplit == 1) return e;
+    const int64_t threads = M * (L.Np / 4);
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, partial, ksplit, M, blob, L,
+                       sx, lorc, Y, ldy, out_dtype);
     return hipGetLastError();
 }
 
 template <bool EXACT>
 hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
-                       void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+                       void* Y, int64_t ldy, int out_dtype, void* workspace, hipStream_t s)
 {
-    // 256 x 256 tiles (8 waves, one workgroup per compute unit) once they fill the 256 compute units
-    // at least ~1.5 times, or fill three quarters of them in a single round; else 128 x 128 (4 waves,
-    // two workgroups per compute unit) if there are enough of those; else 64 x 128, which also serves
-    // 16 < M <= 64, where the kernel is a weight stream.
-    constexpr int64_t kCUs = 256;  // MI355X
-    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((L.Np + bn - 1) / bn); };
-    const int64_t n256 = tiles(256, 256);
-    if (n256 >= kCUs * 3 / 2 || (n256 <= kCUs && n256 * 4 >= kCUs * 3)) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
-    if (M > 64 && tiles(128, 128) >= 384) return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
-    return launch_cfg<2, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    TilePlan p = plan_tiles(M, L.Np, L.nkt);
+    if (workspace == nullptr) { p.ksplit = 1; p.kslice = (int)L.nkt; }  // no room for partial tiles: one slice
+    float* ws = static_cast<float*>(workspace);
+    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    return launch_cfg<2, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
 }
 
 }  // namespace
@@ -551,10 +592,10 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
 bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 16 && L.N >= 64; }
 
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
-                            Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
+                            Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s)
 {
-    return accum == 0 ? launch_pick<true>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s)
-                      : launch_pick<false>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
+    return accum == 0 ? launch_pick<true>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, workspace, s)
+                      : launch_pick<false>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, workspace, s);
 }
 
 }  // namespace zqfp

@@ -19,7 +19,8 @@ int hip_fail(hipError_t e)
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
-                const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum, void* stream)
+                const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace,
+                void* stream)
 {
     if (M < 0 || N < 0 || r < 0 || r > 64) return ZQFP_E_SHAPE;
     zqfp::BlobLayout L;
@@ -30,14 +31,15 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
     if (!Xq || !sx || !packed || !Y) return ZQFP_E_NULL;
     if (r > 0 && (!T || !V)) return ZQFP_E_NULL;
     if (ldy < N) return ZQFP_E_SHAPE;
-    if (!aligned16(Xq) || !aligned16(Y) || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return ZQFP_E_ALIGN;
+    if (!aligned16(Xq) || !aligned16(Y) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0)
+        return ZQFP_E_ALIGN;
     zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* blob = static_cast<const uint8_t*>(packed);
     hipError_t e = zqfp::gemm_decode_supported(M, L)
                        ? zqfp::launch_gemm_decode(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
                    : zqfp::gemm_tile_supported(M, L)
-                       ? zqfp::launch_gemm_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                       ? zqfp::launch_gemm_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, workspace, s)
                        : zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
@@ -111,23 +113,24 @@ int zqfp_unpack_codes(const void* packed, int64_t K, int64_t N, int G, uint8_t* 
 
 size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N)
 {
-    (void)M; (void)K; (void)N;
-    return 0;  // both GEMM forms reduce inside the workgroup
+    // only the tiled form with a K-split uses one: float32 partial tiles, one set per slice of K
+    if (M <= 16 || N < 64 || K <= 0 || K % 128 != 0) return 0;
+    const int64_t Np = (N + 15) / 16 * 16;
+    const zqfp::TilePlan p = zqfp::plan_tiles(M, Np, K / 128);
+    return p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)Np * sizeof(float) : 0;
 }
 
 int zqfp_w4a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
                    void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, void* stream)
 {
-    (void)workspace;
-    return gemm_common(Xq, sx, M, K, packed, N, G, nullptr, nullptr, 0, Y, ldy, out_dtype, accum, stream);
+    return gemm_common(Xq, sx, M, K, packed, N, G, nullptr, nullptr, 0, Y, ldy, out_dtype, accum, workspace, stream);
 }
 
 int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
                         const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum,
                         void* workspace, void* stream)
 {
-    (void)workspace;
-    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, stream);
+    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, stream);
 }
 
 int zqfp_probe_stream_read(const void* src, int64_t bytes, void* sink, int workgroups, void* stream)

@@ -102,6 +102,38 @@ __device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i&
     }
 }
 
+// Tile shape and K-split of the tiled GEMM for a problem size (the launcher and the workspace query
+// must agree).  256 x 256 tiles (8 waves, one workgroup per compute unit) once they fill the 256
+// compute units at least ~1.5 times, or three quarters of them in a single round; else 128 x 128
+// (4 waves, two workgroups per compute unit) if there are enough of those; else 64 x 128, which also
+// serves 16 < M <= 64, where the kernel is a weight stream.  When even those tiles fill less than a
+// third of the chip (few output channels, long K: down-projections at small M), K is cut into
+// `ksplit` slices of `kslice` k-tiles, each tile-slice goes to its own workgroup, and the float32
+// partial tiles meet in a workspace (ksplit * M * Np floats) that a second kernel sums in fixed order.
+struct TilePlan {
+    int bm, bn;       // tile shape
+    int ksplit;       // number of K slices (1: none)
+    int kslice;       // k-tiles per slice
+};
+inline TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
+{
+    constexpr int64_t kCUs = 256;  // MI355X
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((Np + bn - 1) / bn); };
+    TilePlan p{64, 128, 1, (int)nkt};
+    const int64_t n256 = tiles(256, 256);
+    if (n256 >= kCUs * 3 / 2 || (n256 <= kCUs && n256 * 4 >= kCUs * 3)) { p.bm = 256; p.bn = 256; return p; }
+    if (M > 64 && tiles(128, 128) >= 384) { p.bm = 128; p.bn = 128; return p; }
+    const int64_t slots = 2 * kCUs, nt = tiles(64, 128);
+    int64_t want = slots / nt;
+    if (want > 16) want = 16;
+    if (want > nkt / 8) want = nkt / 8;  // a slice is at least 8 k-steps
+    if (want >= 3) {
+        p.kslice = (int)((nkt + want - 1) / want);
+        p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
+    }
+    return p;
+}
+
 // LoRC arguments of the GEMM epilogue (r == 0: none)
 struct Lorc {
     const float* T;     // [M, r]
@@ -121,9 +153,10 @@ hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* code
 hipError_t launch_gemm_stream(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                               int accum, hipStream_t s);
+// workspace: device memory of plan_tiles(...).ksplit * M * Np floats, or nullptr (then K is not split)
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                             const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
-                            int accum, hipStream_t s);
+                            int accum, void* workspace, hipStream_t s);
 bool gemm_tile_supported(int64_t M, const BlobLayout& L);
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,

@@ -201,6 +201,9 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (48, 128, 64, 32, 1, 2),        # a single k-step (no load pipeline to speak of), groups of 32
     (130, 256, 300, 64, 2, 0),      # two k-steps, groups of 64
     (20, 8320, 48, 128, 1, 0),      # N < 64: streaming fallback
+    (64, 4096, 128, 128, 1, 8),     # one 64 x 128 tile, long K: K split 4 ways through the workspace, LoRC in the reduce
+    (100, 3072, 136, 128, 1, 3),    # 4 tiles, K split 3 ways, ragged M and N
+    (33, 11008, 256, 128, 2, 0),    # a down-projection's K (86 k-tiles): uneven slices
 ])
 def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
@@ -353,3 +356,22 @@ def test_fused_rmsnorm_quantizer_argument_checks():
         zqfp.rmsnorm_quantize_act_fp8(X, g, 0.0)
     with pytest.raises(zqfp.ZqfpError):
         zqfp.rmsnorm_quantize_act_fp8(X, g[:128].contiguous(), 1e-5)
+
+
+def test_gemm_k_split_is_optional_and_agrees_with_the_unsplit_launch():
+    """Without a workspace the same call runs un-split; both results meet the parity bar and the
+    workspace query names a size exactly when a split is planned."""
+    M, K, N, G = 64, 4096, 128, 128
+    assert zqfp.gemm_workspace_bytes(M, K, N) == 4 * M * N * 4
+    assert zqfp.gemm_workspace_bytes(4096, 4096, 12288) == 0 and zqfp.gemm_workspace_bytes(16, 8192, 28672) == 0
+    cfg = inputs.Config("t", K, N, (M,), G, 1, 0.01, 0, 20.0, 0, 0)
+    X = inputs.make_x(cfg, M)
+    W, packed = _weights(cfg, G, 1)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    codes_o, exps_o, c_o, _ = oracle.pack_weight(W, G, 1)
+    Y_o, Sabs = oracle.gemm(Xq_o, sx_o, codes_o, exps_o, c_o, G)
+    Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(X))
+    Y_split = _sync_np(zqfp.w4a8_gemm(Xq, sx, packed, N, G))
+    Y_plain = _sync_np(zqfp.w4a8_gemm(Xq, sx, packed, N, G, workspace=torch.empty(0, dtype=torch.uint8, device="cuda")))
+    check_gemm(Y_split, Y_o, Sabs, "K split")
+    check_gemm(Y_plain, Y_o, Sabs, "no workspace")
