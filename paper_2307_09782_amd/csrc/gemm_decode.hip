@@ -34,7 +34,7 @@ __device__ inline uint16_t f32_to_bf16_bits(float f)
 template <int NW, int KPW, int NB, bool EXACT, bool LR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void k_gemm_decode(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int M, const uint8_t* __restrict__ blob, BlobLayout L,
-    Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype)
+    Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len, float* __restrict__ partial)
 {
     constexpr int kWaves = NW;
     constexpr bool HI_LDS = EXACT && KPW >= 8;
@@ -44,8 +44,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: fragment addresses stay in SGPRs
     const int col = lane & 15, lb = lane >> 4;
-    const int nkt = (int)L.nkt;
     const int64_t nstrips = L.nstrips;
+    // A K of more than 64 k-tiles is served in chunks: workgroup b takes chunk b % nchunks, multiplies
+    // its k-tiles kt0 .. kt0 + nkt only and leaves raw float32 sums in slice `chunk` of the workspace.
+    const int nkt_all = (int)L.nkt;
+    const int chunk = nchunks > 1 ? (int)(blockIdx.x % nchunks) : 0;
+    const int kt0 = chunk * chunk_len;
+    const int nkt = min(chunk_len, nkt_all - kt0);
+    const bool raw = nchunks > 1;
+    if (raw) {
+        Y = partial + (int64_t)chunk * M * L.Np;
+        ldy = L.Np;
+        out_dtype = 0;
+    }
 
     // ---- activation fragments: lane (row = lane%16, lb) holds bytes k = 16*lb + [0,16) and
     // k = 64 + 16*lb + [0,16) of each of its k-tiles.  The loads are unconditional: a row past M
@@ -61,7 +72,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
     for (int u = 0; u < KPW; ++u) {
         const int kt = min(wave + kWaves * u, nkt - 1);
-        const uint8_t* p = Xq + (int64_t)min(col, M - 1) * L.K + (int64_t)kt * 128 + 16 * lb;
+        const uint8_t* p = Xq + (int64_t)min(col, M - 1) * L.K + (int64_t)(kt0 + kt) * 128 + 16 * lb;
         ax0[u] = *reinterpret_cast<const u32x4*>(p);
         ax1[u] = *reinterpret_cast<const u32x4*>(p + 64);
     }
@@ -69,9 +80,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     // a few integer operations, cheaper than holding it in registers)
     const bool small_groups = L.gsb < 4;  // groups of 32 or 64: a shift; else one group per k-tile
     auto stored_group = [&](int u) {
-        const int kt = min(wave + kWaves * u, nkt - 1);
+        const int kt = kt0 + min(wave + kWaves * u, nkt - 1);
         const int a = (kt * 4 + lb) >> (small_groups ? L.gsb_shift : 0);
-        const int b = (int)(((uint32_t)kt * L.gq_magic) >> 16);  // kt / (gsb / 4), exact for kt <= 64
+        const int b = (int)(((uint32_t)kt * L.gq_magic) >> 20);  // kt / (gsb / 4)
         return small_groups ? a : b;
     };
 
@@ -92,7 +103,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int er = (tid >> 4) & 15, ec = tid & 15;
     const bool row_live = tid < 256 && er < M;
     const int rk = lorc.r;
-    float sx_r = sx[min(er, M - 1)], t_r[RMAX];
+    float sx_r = raw ? 1.0f : sx[min(er, M - 1)], t_r[RMAX];  // raw: scales are applied when the chunks are added up
 #pragma unroll
     for (int j = 0; j < RMAX; ++j) t_r[j] = 0.f;
     if constexpr (LR) {
@@ -111,7 +122,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
             const int kt = min(wave + kWaves * u, nkt - 1);  // clamped duplicates are multiplied by zero fragments
-            b[buf][u] = reinterpret_cast<const u32x4*>(codes + ((strip * nkt + kt) << 10))[lane];
+            b[buf][u] = reinterpret_cast<const u32x4*>(codes + ((strip * nkt_all + kt0 + kt) << 10))[lane];
             e[buf][u] = (exq + strip * L.ngq * 16)[(stored_group(u) >> 2) * 16 + col];
         }
         const int64_t n = min(strip * 16 + ec, L.N - 1);
@@ -157,7 +168,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         float a = 0.f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) a += s_red[par][w][src][reg];
-        float y = (sx_r * cs[buf]) * a;
+        float y = (sx_r * (raw ? 1.0f : cs[buf])) * a;
         if constexpr (LR) {
 #pragma unroll
             for (int j = 0; j < RMAX; ++j) y = fmaf(t_r[j], j < rk ? half_bits_to_f32((uint16_t)vv[buf][j]) : 0.f, y);
@@ -175,8 +186,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     // The loop is unrolled by NB so that the fragment buffers are addressed statically.  The LDS
     // reduction buffer alternates per strip: it is rewritten two strips later, after a barrier
     // that every reader has passed.
-    const int64_t stride = gridDim.x;
-    int64_t s = blockIdx.x;
+    const int64_t stride = gridDim.x / nchunks;  // workgroups per chunk
+    int64_t s = blockIdx.x / nchunks;
 #pragma unroll
     for (int r = 0; r < NB - 1; ++r) issue(r, s + r * stride);
 #pragma unroll
@@ -214,7 +225,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 
 template <int NW, int KPW, int NB>
 hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
-                const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+                const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len,
+                float* partial, hipStream_t s)
 {
     // LoRC operands of ranks up to 8 are held in registers
     const bool lr = lorc.r > 0 && lorc.r <= 8;
@@ -234,7 +246,7 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
         }
     }
 #define ZQ_LAUNCH(EX, LR) \
-    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype)
+    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial)
     if (exact) { if (lr) ZQ_LAUNCH(true, true); else ZQ_LAUNCH(true, false); }
     else       { if (lr) ZQ_LAUNCH(false, true); else ZQ_LAUNCH(false, false); }
 #undef ZQ_LAUNCH
@@ -243,10 +255,17 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
 
 }  // namespace
 
-bool gemm_decode_supported(int64_t M, const BlobLayout& L) { return M >= 1 && M <= 16 && L.nkt <= 64; }  // gq_magic is exact up to 64 k-tiles
+bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace)
+{
+    if (M < 1 || M > 16) return false;
+    if (L.nkt <= 64) return true;
+    // longer K: in chunks through the workspace, if there are strips enough to give every workgroup
+    // several (below that the streaming kernel, one launch and no prologue per chunk, is faster)
+    return workspace != nullptr && L.nstrips * plan_decode(L.nkt).chunks >= 1024;
+}
 
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
-                              Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
+                              Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s)
 {
     if (L.N == 0) return hipSuccess;
     static int cus = 0;  // compute units of the (single) device, asked once
@@ -259,13 +278,22 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
     }
     const bool exact = accum == 0;
     const int m = (int)M;
-    const int nkt = (int)L.nkt;
-    const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);  // one persistent workgroup per compute unit
-    if (nkt <= 8) return launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    if (nkt <= 16) return launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    if (nkt <= 32) return launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    if (nkt <= 40) return launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
-    return launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, s);
+    const DecodePlan plan = plan_decode(L.nkt);
+    const int nch = plan.chunks, len = plan.len;
+    float* partial = nch > 1 ? static_cast<float*>(workspace) : nullptr;
+    const Lorc none{nullptr, nullptr, 0};
+    const Lorc lk = nch > 1 ? none : lorc;  // with chunks, LoRC is added when they are summed
+    // one persistent workgroup per compute unit, the same number for every chunk
+    const int64_t per_chunk = L.nstrips < cus / nch ? L.nstrips : cus / nch;
+    const unsigned grid = (unsigned)(per_chunk * nch);
+    hipError_t e;
+    if (len <= 8) e = launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 16) e = launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 32) e = launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 40) e = launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else e = launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    if (e != hipSuccess || nch == 1) return e;
+    return launch_splitk_reduce(partial, nch, M, blob, L, sx, lorc, Y, ldy, out_dtype, s);
 }
 
 }  // namespace zqfp

@@ -569,10 +569,7 @@ hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8
                        out_dtype, tiles_m, tiles_n, ksplit, kslice, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || ksplit == 1) return e;
-    const int64_t threads = M * (L.Np / 4);
-    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, partial, ksplit, M, blob, L,
-                       sx, lorc, Y, ldy, out_dtype);
-    return hipGetLastError();
+    return launch_splitk_reduce(partial, ksplit, M, blob, L, sx, lorc, Y, ldy, out_dtype, s);
 }
 
 template <bool EXACT>
@@ -588,6 +585,15 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
 }
 
 }  // namespace
+
+hipError_t launch_splitk_reduce(const float* partial, int slices, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                                const float* sx, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+{
+    const int64_t threads = M * (L.Np / 4);
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, partial, slices, M, blob, L,
+                       sx, lorc, Y, ldy, out_dtype);
+    return hipGetLastError();
+}
 
 bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 16 && L.N >= 64; }
 

@@ -36,8 +36,8 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
     zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* blob = static_cast<const uint8_t*>(packed);
-    hipError_t e = zqfp::gemm_decode_supported(M, L)
-                       ? zqfp::launch_gemm_decode(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+    hipError_t e = zqfp::gemm_decode_supported(M, L, workspace)
+                       ? zqfp::launch_gemm_decode(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, workspace, s)
                    : zqfp::gemm_tile_supported(M, L)
                        ? zqfp::launch_gemm_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, workspace, s)
                        : zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
@@ -114,8 +114,13 @@ int zqfp_unpack_codes(const void* packed, int64_t K, int64_t N, int G, uint8_t* 
 size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N)
 {
     // only the tiled form with a K-split uses one: float32 partial tiles, one set per slice of K
-    if (M <= 16 || N < 64 || K <= 0 || K % 128 != 0) return 0;
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
     const int64_t Np = (N + 15) / 16 * 16;
+    if (M <= 16) {  // decode form: K beyond 64 k-tiles is served in chunks
+        const zqfp::DecodePlan d = zqfp::plan_decode(K / 128);
+        return d.chunks > 1 ? (size_t)d.chunks * (size_t)M * (size_t)Np * sizeof(float) : 0;
+    }
+    if (N < 64) return 0;
     const zqfp::TilePlan p = zqfp::plan_tiles(M, Np, K / 128);
     return p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)Np * sizeof(float) : 0;
 }

@@ -45,7 +45,7 @@ struct BlobLayout {
     int G, Gs, ngs, ngq;
     int gsb;        // 32-element blocks per stored group (Gs / 32)
     int gsb_shift;  // log2(gsb) if gsb is a power of two, else -1
-    uint32_t gq_magic;  // groups of >= 128: stored group of k-tile kt is (kt * gq_magic) >> 16 for kt <= 64
+    uint32_t gq_magic;  // groups of >= 128: stored group of k-tile kt is (kt * gq_magic) >> 20 (exact for kt < 16384)
     size_t off_codes, off_exps, off_colscale, total;
 };
 
@@ -65,7 +65,7 @@ inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
     for (int s = 0; s < 16; ++s) if ((1 << s) == L->gsb) L->gsb_shift = s;
     {
         const int gq = L->gsb >= 4 ? L->gsb / 4 : 1;  // k-tiles per stored group
-        L->gq_magic = (uint32_t)((65536 + gq - 1) / gq);
+        L->gq_magic = (uint32_t)(((1 << 20) + gq - 1) / gq);  // gq <= 64, so kt * gq_magic < 2^32 for kt < 4096
     }
     L->off_codes = 256;
     L->off_exps = L->off_codes + (size_t)L->Np * (size_t)K / 2;
@@ -134,6 +134,19 @@ inline TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
     return p;
 }
 
+// The decode GEMM keeps a wave's activation fragments in registers, at most 8 k-tiles per wave and
+// 64 per workgroup.  A longer K is cut into `chunks` pieces of `len` k-tiles; a workgroup serves one
+// piece, and the float32 partial results meet in the caller's workspace ([chunks][M][Np]) like
+// the K slices of the tiled form.
+struct DecodePlan { int chunks, len; };
+inline DecodePlan plan_decode(int64_t nkt)
+{
+    DecodePlan p;
+    p.chunks = (int)((nkt + 63) / 64);
+    p.len = (int)((nkt + p.chunks - 1) / p.chunks);
+    return p;
+}
+
 // LoRC arguments of the GEMM epilogue (r == 0: none)
 struct Lorc {
     const float* T;     // [M, r]
@@ -158,10 +171,14 @@ hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const
                             const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                             int accum, void* workspace, hipStream_t s);
 bool gemm_tile_supported(int64_t M, const BlobLayout& L);
+// workspace: plan_decode(nkt).chunks * M * Np floats when K has more than 64 k-tiles (else unused)
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
-                              int accum, hipStream_t s);
-bool gemm_decode_supported(int64_t M, const BlobLayout& L);
+                              int accum, void* workspace, hipStream_t s);
+bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace);
+// Y[m,n] = (sx[m] c[n]) * sum_s partial[s][m][n] (+ T.V): the second kernel of every K-split
+hipError_t launch_splitk_reduce(const float* partial, int slices, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                                const float* sx, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s);
 hipError_t launch_probe_read(const void* src, int64_t bytes, uint32_t* sink, int workgroups, hipStream_t s);
 hipError_t launch_probe_mfma(const uint32_t* operands, float* sink, int iters, int workgroups, hipStream_t s);
 

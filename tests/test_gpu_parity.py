@@ -204,6 +204,9 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (64, 4096, 128, 128, 1, 8),     # one 64 x 128 tile, long K: K split 4 ways through the workspace, LoRC in the reduce
     (100, 3072, 136, 128, 1, 3),    # 4 tiles, K split 3 ways, ragged M and N
     (33, 11008, 256, 128, 2, 0),    # a down-projection's K (86 k-tiles): uneven slices
+    (16, 11008, 96, 128, 1, 8),     # M <= 16 beyond 64 k-tiles, few strips: streaming fallback with LoRC
+    (3, 8320, 80, 64, 2, 0),        # the same with 65 k-tiles, groups of 64
+    (9, 28672, 48, 128, 1, 0),      # the same with 224 k-tiles
 ])
 def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
@@ -375,3 +378,20 @@ def test_gemm_k_split_is_optional_and_agrees_with_the_unsplit_launch():
     Y_plain = _sync_np(zqfp.w4a8_gemm(Xq, sx, packed, N, G, workspace=torch.empty(0, dtype=torch.uint8, device="cuda")))
     check_gemm(Y_split, Y_o, Sabs, "K split")
     check_gemm(Y_plain, Y_o, Sabs, "no workspace")
+    # M <= 16 beyond 64 k-tiles: a workspace is named; with few strips both calls take the streaming kernel
+    assert zqfp.gemm_workspace_bytes(8, 8320, 128) == 2 * 8 * 128 * 4
+    Yd = _sync_np(zqfp.w4a8_gemm(Xq[:8].contiguous(), sx[:8].contiguous(), packed, N, G))
+    Yd0 = _sync_np(zqfp.w4a8_gemm(Xq[:8].contiguous(), sx[:8].contiguous(), packed, N, G,
+                                  workspace=torch.empty(0, dtype=torch.uint8, device="cuda")))
+    check_gemm(Yd, Y_o[:8], Sabs[:8], "decode")
+    check_gemm(Yd0, Y_o[:8], Sabs[:8], "decode, no workspace")
+
+
+@pytest.mark.parametrize("M,K,N,G,mode,r", [(16, 8320, 8192, 64, 2, 8),     # 65 k-tiles: chunks of 33 and 32
+                                            (5, 16640, 5504, 128, 1, 0)])   # 130 k-tiles: three chunks of 44, 44, 42
+def test_gemm_decode_long_k_in_chunks(M, K, N, G, mode, r):
+    """Decode form with more than 64 k-tiles and strips enough for the chunked path (partial sums
+    through the workspace, scales and LoRC in the reduce kernel); sampled outputs."""
+    assert zqfp.gemm_workspace_bytes(M, K, N) == -(-K // 128 // 64) * M * N * 4
+    Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r, seed_cfg="llama70b_ffn_decode", full=False, nsamples=2048)
+    check_gemm(Y, Y_o, Sabs, f"decode chunks M{M} K{K} N{N}")
