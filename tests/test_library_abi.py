@@ -94,3 +94,19 @@ def test_build_rejects_spills_in_hand_scheduled_kernels():
     bad = ok.replace("ScratchSize [bytes/lane]: 0", "ScratchSize [bytes/lane]: 24")
     with pytest.raises(RuntimeError):
         build._check_no_scratch(bad)
+
+
+def test_workspace_query_is_pure_host_logic():
+    """zqfp_gemm_workspace_bytes plans on the host (no GPU needed): zero for every benchmark
+    configuration, [slices][M][Np] floats where K is split."""
+    lib = zqfp.lib()
+    ws = lambda M, K, N: int(lib.zqfp_gemm_workspace_bytes(M, K, N))
+    for (M, K, N) in [(16, 256, 256), (2048, 2048, 8192), (1, 4096, 12288), (16, 4096, 12288), (256, 4096, 12288),
+                      (4096, 4096, 12288), (4096, 4096, 11008), (16, 5120, 13824), (2048, 5120, 13824),
+                      (1, 8192, 28672), (4, 8192, 28672), (16, 8192, 28672), (64, 8192, 28672)]:
+        assert ws(M, K, N) == 0, (M, K, N)
+    assert ws(64, 4096, 128) == 4 * 64 * 128 * 4          # one tile, 32 k-tiles: 4 slices of 8
+    assert ws(64, 11008, 4096) == 10 * 64 * 4096 * 4      # 32 tiles, 86 k-tiles: 10 slices of 9
+    assert ws(100, 3072, 136) == 3 * 100 * 144 * 4        # Np = 144
+    assert ws(16, 28672, 8192) == 4 * 16 * 8192 * 4       # decode form: 224 k-tiles in 4 chunks
+    assert ws(8, 8192, 4096) == 0 and ws(0, 4096, 4096) == 0 and ws(64, 4100, 4096) == 0
