@@ -1,14 +1,14 @@
-// W4A8 GEMM, tiled form for many tokens (prefill): bound by the FP8 matrix
-// cores.
+// W4A8 GEMM, tiled form for more than 16 tokens: bound by the FP8 matrix cores
+// when the tokens are many (prefill), a weight stream when they are few.
 //
 //   Y[m,n] = (sx[m] c[n]) * sum_k a[m,k] * q[k,n] * 2^e[g(k),n]   (+ T.V, LoRC)
 //
 // (paper Sections 1 and 3.)  A workgroup of WAVES_M x WAVES_N waves owns a
 // BM x BN output tile; each wave owns WTM x WTN tiles of 16 x 16 and walks K in
 // steps of 128 with v_mfma_scale_f32_16x16x128_f8f6f4 (A = E4M3 from LDS,
-// B = packed E2M1 from LDS, B's E8M0 group exponent straight from global
-// memory into the instruction's scale operand -- the FP4 -> FP8 alignment is
-// done by the matrix core, no unpack and no multiply).
+// B = packed E2M1 from LDS, B's E8M0 group exponent, also through LDS, in the
+// instruction's scale operand -- the FP4 -> FP8 alignment is done by the
+// matrix core, no unpack and no multiply).
 //
 // Two waves share a SIMD so that one wave's LDS reads and barrier waits hide
 // behind the other's matrix instructions.  LDS holds three stages.  A stage
