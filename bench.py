@@ -294,7 +294,7 @@ def main():
                     help="also run one 1 GiB device copy (yardstick for rocprofv3 HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)")
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here uses a second GPU)")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     zqfp.lib()  # fail loudly if the HIP library has not been built
