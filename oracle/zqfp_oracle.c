@@ -25,7 +25,7 @@
  *   lorc         : Section 3 (LoRC: the low-rank product U.V is added to the
  *                  quantized weight), Appendix A (rank 8 for LLaMA).
  *
- * Readings taken where the paper is silent (listed in the design document):
+ * Readings taken where the paper is silent:
  *   - S = absmax / format_max (448 for E4M3, 6 for E2M1), symmetric (Z = 0).
  *   - E4M3 is the OCP "FN" flavour: bias 7, no infinities, S.1111.111 = NaN,
  *     max finite 448.
