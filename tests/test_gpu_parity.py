@@ -395,3 +395,23 @@ def test_gemm_decode_long_k_in_chunks(M, K, N, G, mode, r):
     assert zqfp.gemm_workspace_bytes(M, K, N) == -(-K // 128 // 64) * M * N * 4
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r, seed_cfg="llama70b_ffn_decode", full=False, nsamples=2048)
     check_gemm(Y, Y_o, Sabs, f"decode chunks M{M} K{K} N{N}")
+
+
+def test_gemm_seeded_sweep_of_small_shapes():
+    """Forty seeded random shapes across every dispatch branch (decode form, chunked K, streaming
+    fallback, the three tile shapes' smallest members, K split), each compared in full with the oracle."""
+    rng = np.random.default_rng(20230719)
+    done = 0
+    while done < 40:
+        M = int(rng.choice([1, 2, 7, 16, 17, 31, 64, 65, 100, 129, 257]))
+        K = 128 * int(rng.integers(1, 72))
+        N = int(rng.choice([1, 15, 16, 63, 64, 65, 127, 128, 200, 272, 513]))
+        Gs = [g for g in (32, 64, 128, 256, 384, K) if K % g == 0 and K // g <= 256]
+        G = int(rng.choice(Gs))
+        mode = int(rng.integers(1, 3))
+        r = int(rng.choice([0, 0, 3, 8, 16]))
+        if M * K * N > 3.0e8:
+            continue
+        Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
+        check_gemm(Y, Y_o, Sabs, f"sweep M{M} K{K} N{N} G{G} mode{mode} r{r}")
+        done += 1
