@@ -71,6 +71,8 @@ def lib():
         L.orc_lorc_left.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int, p, p]
         L.orc_rmsnorm_bf16.restype = None
         L.orc_rmsnorm_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_float, p]
+        L.orc_layernorm_bf16.restype = None
+        L.orc_layernorm_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, p, c.c_float, p]
         L.orc_max_threads.restype = c.c_int
         L.orc_max_threads.argtypes = []
         _lib = L
@@ -135,6 +137,17 @@ def rmsnorm_bf16(X, g, eps):
         raise ValueError("gain length / eps")
     Y = np.empty((M, K), np.uint16)
     lib().orc_rmsnorm_bf16(_ptr(X), M, K, K, _ptr(g), float(eps), _ptr(Y))
+    return Y
+
+
+def layernorm_bf16(X, g, b, eps):
+    """Layer normalisation of bf16 rows (bits) with bf16 gain g and bias b, result rounded to bf16 (bits)."""
+    _chk(X, np.uint16, 2), _chk(g, np.uint16, 1), _chk(b, np.uint16, 1)
+    M, K = X.shape
+    if g.shape[0] != K or b.shape[0] != K or not eps > 0:
+        raise ValueError("gain / bias length or eps")
+    Y = np.empty((M, K), np.uint16)
+    lib().orc_layernorm_bf16(_ptr(X), M, K, K, _ptr(g), _ptr(b), float(eps), _ptr(Y))
     return Y
 
 

@@ -20,8 +20,8 @@
  *   gemm         : the W4A8 linear layer the cast exists for (Sections 1, 3):
  *                  Y = Q8(X) . Q4(W), written out as the plain definition with
  *                  an fp64 sum.
- *   rmsnorm      : the normalisation whose output Section 3 quantizes (textbook
- *                  definition; see orc_rmsnorm_bf16).
+ *   rmsnorm,     : the normalisations whose output Section 3 quantizes (textbook
+ *   layernorm      definitions; see orc_rmsnorm_bf16, orc_layernorm_bf16).
  *   lorc         : Section 3 (LoRC: the low-rank product U.V is added to the
  *                  quantized weight), Appendix A (rank 8 for LLaMA).
  *
@@ -269,6 +269,47 @@ void orc_rmsnorm_bf16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
             volatile float a = bf16_bits_to_f32(row[k]) * rstd;
             volatile float b = a * bf16_bits_to_f32(g[k]);
             Y[m * K + k] = f32_to_bf16_bits_rne(b);
+        }
+    }
+}
+
+/* Layer normalisation, the producer the paper names for the OPT models it
+ * inspects (Section 3, "Distribution of Activations": attn.q_proj and fc1 inputs
+ * come out of "layer-normalization").  Textbook definition,
+ *     y[k] = (x[k] - mean) / sqrt(var + eps) * g[k] + b[k],
+ *     mean = sum x / K,  var = sum x^2 / K - mean^2  (population variance),
+ * result rounded to bfloat16.  Fixed arithmetic: both sums, the mean and the
+ * variance (clamped at 0) in binary64; then binary32 steps, each rounded once,
+ *     mu = fl32(mean); v = fl32(var); rstd = 1 / sqrt(v + eps);
+ *     y = bf16_rne( ((x - mu) * rstd) * g + b ).
+ * eps must be positive.  X: M x K bf16 bits, row stride ldx.  g, b: K bf16 bits.
+ * Y: M x K bf16 bits, dense. */
+void orc_layernorm_bf16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                        const uint16_t *g, const uint16_t *b, float eps, uint16_t *Y)
+{
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *row = X + m * ldx;
+        double s1 = 0.0, s2 = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double x = (double)bf16_bits_to_f32(row[k]);
+            s1 += x;
+            s2 += x * x;
+        }
+        double mean = s1 / (double)K;
+        double var = s2 / (double)K - mean * mean;
+        if (var < 0.0)
+            var = 0.0;
+        volatile float mu = (float)mean;
+        volatile float v = (float)var;
+        volatile float t = v + eps;
+        volatile float sd = sqrtf(t);
+        volatile float rstd = 1.0f / sd;
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float d = bf16_bits_to_f32(row[k]) - mu;
+            volatile float a = d * rstd;
+            volatile float c = a * bf16_bits_to_f32(g[k]);
+            volatile float e = c + bf16_bits_to_f32(b[k]);
+            Y[m * K + k] = f32_to_bf16_bits_rne(e);
         }
     }
 }
