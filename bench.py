@@ -189,16 +189,18 @@ def calibration_copy(nbytes=1 << 30):
 
 
 def quantizer_rows(name="llama7b_qkv", M=4096):
-    """The quantizer alone and fused behind RMS normalisation, HBM-bound (2 B read + 1 B written per
+    """The quantizer alone and fused behind RMS or layer normalisation, HBM-bound (2 B read + 1 B written per
     element): one HIP graph of calls rotating through input copies that exceed the last-level cache."""
     cfg = inputs.CONFIGS[name]
     X = bf16_dev(inputs.make_x(cfg, M))
     copies = max(1, -(-600_000_000 // (2 * M * cfg.K)))
     Xs = [X] + [X.clone() for _ in range(copies - 1)]
     gain = torch.ones(cfg.K, dtype=torch.bfloat16, device="cuda")
+    bias = torch.zeros(cfg.K, dtype=torch.bfloat16, device="cuda")
     rows = []
     for label, fn in (("quantize_act_fp8", lambda x: zqfp.quantize_act_fp8(x)),
-                      ("rmsnorm_quantize_act_fp8", lambda x: zqfp.rmsnorm_quantize_act_fp8(x, gain, 1e-5))):
+                      ("rmsnorm_quantize_act_fp8", lambda x: zqfp.rmsnorm_quantize_act_fp8(x, gain, 1e-5)),
+                      ("layernorm_quantize_act_fp8", lambda x: zqfp.layernorm_quantize_act_fp8(x, gain, bias, 1e-5))):
         for x in Xs[:2]:
             fn(x)
         torch.cuda.synchronize()
@@ -215,7 +217,7 @@ def quantizer_rows(name="llama7b_qkv", M=4096):
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / (5 * len(Xs))
-        nbytes = 3 * M * cfg.K + 4 * M + (2 * cfg.K if label.startswith("rms") else 0)
+        nbytes = 3 * M * cfg.K + 4 * M + {"q": 0, "r": 2 * cfg.K, "l": 4 * cfg.K}[label[0]]
         gbs = nbytes / (ms * 1e-3) / 1e9
         rows.append({"call": label, "workload": f"{M}x{cfg.K} bf16", "ms": round(ms, 5), "gbs": round(gbs, 1),
                      "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "input_copies_rotated": len(Xs)})

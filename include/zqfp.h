@@ -123,6 +123,30 @@ int zqfp_rmsnorm_quantize_act_fp8(const void *X, const void *gain, float eps,
                                   const void *U, int r, float *T, void *stream);
 
 /*
+ * layernorm_quantize_act_fp8 -- the same, behind a layer normalisation with
+ * gain and bias (paper Section 3, "Distribution of Activations": the inputs of
+ * attn.q_proj and fc1 are layer-normalisation outputs; the form the OPT models
+ * of Section 4 use):
+ *
+ *   y[m,k] = bf16( (X[m,k] - mean_m) / sqrt(var_m + eps) * gain[k] + bias[k] )
+ *
+ * with the population variance var_m = mean_k X^2 - mean_m^2 (clamped at 0).
+ * Sums of x and x^2, the mean and the variance in binary64; then, in IEEE
+ * binary32, mu = fl(mean), v = fl(var), rstd = 1 / sqrt(v + eps),
+ * y = bf16_rne(((x - mu) * rstd) * gain + bias), each operation rounded on its
+ * own.  The codes and scales are those of the unfused sequence, bit for bit.
+ *
+ *   gain, bias  [K] bfloat16 each (device, 16-byte aligned)            (in)
+ * Other arguments, limits and errors as for zqfp_rmsnorm_quantize_act_fp8.
+ */
+int zqfp_layernorm_quantize_act_fp8(const void *X, const void *gain,
+                                    const void *bias, float eps,
+                                    int64_t M, int64_t K, int64_t ldx,
+                                    uint8_t *Xq, float *sx,
+                                    const void *U, int r, float *T,
+                                    void *stream);
+
+/*
  * pack_weight_fp4 -- group-wise FP4 (E2M1) weight quantization with
  * power-of-two scales (paper Section 3: fine-grained quantization; "Casting
  * the FP4 to FP8": S = 2^n with methods M1 / M2; Appendix A: group size).

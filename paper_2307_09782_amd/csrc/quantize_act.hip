@@ -1,6 +1,8 @@
 // Token-wise FP8 (E4M3) activation quantizer, with the optional LoRC left
 // factor T = X.U computed in the same sweep (paper Section 3: token-wise
-// activation quantization, LoRC; Appendix A).
+// activation quantization, LoRC; Appendix A).  The normalisation whose output
+// the quantizer sees (Section 3 names the layer normalisation in front of the
+// quantized linear layers; LLaMA uses the RMS form) can run in the same sweep.
 //
 // One workgroup of 256 threads per token (1024 for a handful of tokens).  The row is read once with 16-byte
 // loads (8 bf16 per lane), kept in registers across the absmax reduction
@@ -107,6 +109,50 @@ __device__ inline uint4 normalize8(uint4 v, uint4 g, float rstd)
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// 8 bf16 -> 8 bf16: ((x - mu) * rstd) * g + b, four separately rounded binary32 operations (the
+// product and the sum must not fuse into one), rounded to bf16
+__device__ inline uint4 normalize8_affine(uint4 v, uint4 g, uint4 b, float mu, float rstd)
+{
+#pragma clang fp contract(off)
+    uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {g.x, g.y, g.z, g.w}, bw[4] = {b.x, b.y, b.z, b.w}, o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float dl = bf16_lo(w[i]) - mu, dh = bf16_hi(w[i]) - mu;
+        const float al = dl * rstd, ah = dh * rstd;
+        const float cl = al * bf16_lo(gw[i]), ch = ah * bf16_hi(gw[i]);
+        const float lo = cl + bf16_lo(bw[i]), hi = ch + bf16_hi(bw[i]);
+        o[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ inline double sum_values(double acc, uint4 v)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        acc += (double)bf16_lo(w[i]);
+        acc += (double)bf16_hi(w[i]);
+    }
+    return acc;
+}
+
+// statistics of a row from its two binary64 sums: 1 / sqrt(second moment or variance + eps) in binary32
+// arithmetic (IEEE add, square root, division), and for layer normalisation the mean rounded to binary32
+template <int NORM>
+__device__ inline void row_statistics(double s1, double ss, int64_t K, float eps, float& mu, float& rstd)
+{
+#pragma clang fp contract(off)
+    double second = ss / (double)K;
+    mu = 0.0f;
+    if constexpr (NORM == 2) {
+        const double mean = s1 / (double)K;
+        second = fmax(second - mean * mean, 0.0);  // variance, never negative
+        mu = (float)mean;
+    }
+    rstd = 1.0f / sqrtf((float)second + eps);
+}
+
 __device__ inline double sum_squares(double acc, uint4 v)
 {
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -119,11 +165,13 @@ __device__ inline double sum_squares(double acc, uint4 v)
     return acc;
 }
 
-template <int RP, int NT, bool NORM>
+// NORM: 0 plain quantizer, 1 RMS normalisation (gain) in front, 2 layer normalisation (gain, bias) in front
+template <int RP, int NT, int NORM>
 __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict__ X, int64_t K, int64_t ldx,
                                                          uint8_t* __restrict__ Xq, float* __restrict__ sx,
                                                          const uint16_t* __restrict__ U, int r, float* __restrict__ T,
-                                                         const uint16_t* __restrict__ gain, float eps)
+                                                         const uint16_t* __restrict__ gain,
+                                                         const uint16_t* __restrict__ bias, float eps)
 {
     constexpr int kThreads = NT, kWaves = NT / 64;
     __shared__ uint32_t s_amax[kWaves];
@@ -142,37 +190,60 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
         v[c] = make_uint4(0, 0, 0, 0);
         if (idx < nchunk) v[c] = xrow[idx];
     }
-    if constexpr (NORM) {
+    if constexpr (NORM != 0) {
         // the whole row sits in registers (the launcher guarantees K <= 8 * kRegChunks * NT): sum of
-        // squares in binary64, waves meet in LDS and every thread adds the partial sums in the same
-        // order; then the normalised row replaces the row
-        __shared__ double s_ss[kWaves];
+        // squares (and of the values, for layer normalisation) in binary64, waves meet in LDS and
+        // every thread adds the partial sums in the same order; then the normalised row replaces the row
+        __shared__ double s_ss[kWaves], s_s1[NORM == 2 ? kWaves : 1];
         const uint4* grow = reinterpret_cast<const uint4*>(gain);
-        uint4 g[kRegChunks];
-        double ss = 0.0;
+        const uint4* brow = reinterpret_cast<const uint4*>(bias);
+        uint4 g[kRegChunks], b[NORM == 2 ? kRegChunks : 1];
+        double ss = 0.0, s1 = 0.0;
 #pragma unroll
         for (int c = 0; c < kRegChunks; ++c) {
             int idx = tid + c * kThreads;
             g[c] = make_uint4(0, 0, 0, 0);
             if (idx < nchunk) g[c] = grow[idx];
+            if constexpr (NORM == 2) {
+                b[c] = make_uint4(0, 0, 0, 0);
+                if (idx < nchunk) b[c] = brow[idx];
+                s1 = sum_values(s1, v[c]);
+            }
             ss = sum_squares(ss, v[c]);
         }
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
-        if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
+        for (int off = 32; off > 0; off >>= 1) {
+            ss += __shfl_xor(ss, off);
+            if constexpr (NORM == 2) s1 += __shfl_xor(s1, off);
+        }
+        if ((tid & 63) == 0) {
+            s_ss[tid >> 6] = ss;
+            if constexpr (NORM == 2) s_s1[tid >> 6] = s1;
+        }
         __syncthreads();
         ss = s_ss[0];
+        if constexpr (NORM == 2) s1 = s_s1[0];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) ss += s_ss[w];
-        const float ms = (float)(ss / (double)K);
-        const float rstd = 1.0f / sqrtf(ms + eps);  // IEEE binary32 add, square root, division
+        for (int w = 1; w < kWaves; ++w) {
+            ss += s_ss[w];
+            if constexpr (NORM == 2) s1 += s_s1[w];
+        }
+        float mu, rstd;
+        row_statistics<NORM>(s1, ss, K, eps, mu, rstd);
 #pragma unroll
-        for (int c = 0; c < kRegChunks; ++c) v[c] = normalize8(v[c], g[c], rstd);
+        for (int c = 0; c < kRegChunks; ++c) {
+            if constexpr (NORM == 2) {
+                // chunks past the row's end stay zero: the bias must not leak into the absmax
+                if (tid + c * kThreads < nchunk) v[c] = normalize8_affine(v[c], g[c], b[c], mu, rstd);
+            } else {
+                v[c] = normalize8(v[c], g[c], rstd);
+            }
+        }
     }
     uint32_t am = 0;
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) am = absmax_bits(am, v[c]);
-    if constexpr (!NORM)
+    if constexpr (NORM == 0)
         for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) am = absmax_bits(am, xrow[idx]);
 
     // LoRC left factor first: its loads of U overlap the row's own loads and the absmax reduction.
@@ -195,7 +266,7 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
             int idx = tid + c * kThreads;
             if (idx - lane < nchunk) one_chunk(idx < nchunk ? v[c] : make_uint4(0, 0, 0, 0), idx);
         }
-        if constexpr (!NORM)
+        if constexpr (NORM == 0)
             for (int idx = tid + kRegChunks * kThreads; idx - lane < nchunk; idx += kThreads)
                 one_chunk(idx < nchunk ? xrow[idx] : make_uint4(0, 0, 0, 0), idx);
     }
@@ -221,7 +292,7 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
         int idx = tid + c * kThreads;
         if (idx < nchunk) qrow[idx] = encode8(v[c], inv);
     }
-    if constexpr (!NORM)
+    if constexpr (NORM == 0)
         for (int idx = tid + kRegChunks * kThreads; idx < nchunk; idx += kThreads) qrow[idx] = encode8(xrow[idx], inv);
 
     if constexpr (RP > 0) {
@@ -248,10 +319,11 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
 // the reductions are wave shuffles only, and no barrier or LDS is involved; 16 waves per compute
 // unit keep 8 * MAXC KB of loads in flight each.
 // ---------------------------------------------------------------------------
-template <int MAXC, bool NORM>
+template <int MAXC, int NORM>
 __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
                                                      uint8_t* __restrict__ Xq, float* __restrict__ sx,
-                                                     const uint16_t* __restrict__ gain, float eps)
+                                                     const uint16_t* __restrict__ gain,
+                                                     const uint16_t* __restrict__ bias, float eps)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -267,19 +339,29 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
         v[c] = make_uint4(0, 0, 0, 0);
         if (idx < nchunk) v[c] = xrow[idx];
     }
-    if constexpr (NORM) {
-        double ss = 0.0;
+    if constexpr (NORM != 0) {
+        double ss = 0.0, s1 = 0.0;
 #pragma unroll
-        for (int c = 0; c < MAXC; ++c) ss = sum_squares(ss, v[c]);
+        for (int c = 0; c < MAXC; ++c) {
+            ss = sum_squares(ss, v[c]);
+            if constexpr (NORM == 2) s1 = sum_values(s1, v[c]);
+        }
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);  // every lane ends with the same sum
-        const float ms = (float)(ss / (double)K);
-        const float rstd = 1.0f / sqrtf(ms + eps);  // IEEE binary32 add, square root, division
+        for (int off = 32; off > 0; off >>= 1) {  // every lane ends with the same sums
+            ss += __shfl_xor(ss, off);
+            if constexpr (NORM == 2) s1 += __shfl_xor(s1, off);
+        }
+        float mu, rstd;
+        row_statistics<NORM>(s1, ss, K, eps, mu, rstd);
         const uint4* grow = reinterpret_cast<const uint4*>(gain);
+        const uint4* brow = reinterpret_cast<const uint4*>(bias);
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
             const int idx = c * 64 + lane;
-            if (idx < nchunk) v[c] = normalize8(v[c], grow[idx], rstd);
+            if (idx < nchunk) {
+                if constexpr (NORM == 2) v[c] = normalize8_affine(v[c], grow[idx], brow[idx], mu, rstd);
+                else v[c] = normalize8(v[c], grow[idx], rstd);
+            }
         }
     }
     uint32_t am = 0;
@@ -304,32 +386,44 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
 }  // namespace
 
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx,
-                               const uint16_t* U, int r, float* T, const uint16_t* gain, float eps, hipStream_t s)
+                               const uint16_t* U, int r, float* T, const uint16_t* gain, const uint16_t* bias, float eps,
+                               hipStream_t s)
 {
     if (M == 0) return hipSuccess;
-    const bool norm = gain != nullptr;
+    const int norm = gain == nullptr ? 0 : bias == nullptr ? 1 : 2;
     if (r == 0 && M >= 1024 && K <= 8192) {  // many tokens, no LoRC factor: one wave per token
         const dim3 g4((unsigned)((M + 3) / 4));
-#define ZQ_ROWS(MAXC)                                                                                                  \
-    do {                                                                                                               \
-        if (norm) hipLaunchKernelGGL((k_quantize_rows<MAXC, true>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, eps);  \
-        else hipLaunchKernelGGL((k_quantize_rows<MAXC, false>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, eps);      \
+#define ZQ_ROWS_N(MAXC, NORM) \
+    hipLaunchKernelGGL((k_quantize_rows<MAXC, NORM>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, bias, eps)
+#define ZQ_ROWS(MAXC)                          \
+    do {                                       \
+        if (norm == 2) ZQ_ROWS_N(MAXC, 2);     \
+        else if (norm == 1) ZQ_ROWS_N(MAXC, 1); \
+        else ZQ_ROWS_N(MAXC, 0);               \
     } while (0)
         if (K <= 2048) ZQ_ROWS(4);
         else if (K <= 4096) ZQ_ROWS(8);
         else ZQ_ROWS(16);
 #undef ZQ_ROWS
+#undef ZQ_ROWS_N
         return hipGetLastError();
     }
     const dim3 grid((unsigned)M);
     // 1024 threads per token for a handful of tokens, and for normalised rows too long for 256 threads' registers
-    const bool wide = (M <= 64 && K >= 2048) || (norm && K > 8 * kRegChunks * 256);
-#define ZQ_QUANT(RP)                                                                                                       \
-    do {                                                                                                                   \
-        if (norm && wide) hipLaunchKernelGGL((k_quantize_act<RP, 1024, true>), grid, dim3(1024), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps); \
-        else if (norm) hipLaunchKernelGGL((k_quantize_act<RP, 256, true>), grid, dim3(256), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);      \
-        else if (wide) hipLaunchKernelGGL((k_quantize_act<RP, 1024, false>), grid, dim3(1024), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);   \
-        else hipLaunchKernelGGL((k_quantize_act<RP, 256, false>), grid, dim3(256), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, eps);               \
+    const bool wide = (M <= 64 && K >= 2048) || (norm != 0 && K > 8 * kRegChunks * 256);
+#define ZQ_QUANT_N(RP, NT, NORM) \
+    hipLaunchKernelGGL((k_quantize_act<RP, NT, NORM>), grid, dim3(NT), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, bias, eps)
+#define ZQ_QUANT(RP)                                      \
+    do {                                                  \
+        if (wide) {                                       \
+            if (norm == 2) ZQ_QUANT_N(RP, 1024, 2);       \
+            else if (norm == 1) ZQ_QUANT_N(RP, 1024, 1);  \
+            else ZQ_QUANT_N(RP, 1024, 0);                 \
+        } else {                                          \
+            if (norm == 2) ZQ_QUANT_N(RP, 256, 2);        \
+            else if (norm == 1) ZQ_QUANT_N(RP, 256, 1);   \
+            else ZQ_QUANT_N(RP, 256, 0);                  \
+        }                                                 \
     } while (0)
     if (r == 0) ZQ_QUANT(0);
     else if (r <= 8) ZQ_QUANT(8);
@@ -337,6 +431,7 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
     else if (r <= 32) ZQ_QUANT(32);
     else ZQ_QUANT(64);
 #undef ZQ_QUANT
+#undef ZQ_QUANT_N
     return hipGetLastError();
 }
 

@@ -48,7 +48,7 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
 
 extern "C" {
 
-int zqfp_version(void) { return 101; }
+int zqfp_version(void) { return 102; }
 
 const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
 
@@ -61,7 +61,7 @@ int zqfp_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, uint
     if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
     if (!aligned16(X) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
     hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
-                                             static_cast<const uint16_t*>(U), r, T, nullptr, 0.0f,
+                                             static_cast<const uint16_t*>(U), r, T, nullptr, nullptr, 0.0f,
                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
@@ -75,8 +75,24 @@ int zqfp_rmsnorm_quantize_act_fp8(const void* X, const void* gain, float eps, in
     if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
     if (!aligned16(X) || !aligned16(gain) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
     hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
-                                             static_cast<const uint16_t*>(U), r, T, static_cast<const uint16_t*>(gain), eps,
-                                             static_cast<hipStream_t>(stream));
+                                             static_cast<const uint16_t*>(U), r, T, static_cast<const uint16_t*>(gain), nullptr,
+                                             eps, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_layernorm_quantize_act_fp8(const void* X, const void* gain, const void* bias, float eps, int64_t M, int64_t K,
+                                    int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r, float* T, void* stream)
+{
+    if (M < 0 || K <= 0 || K % 128 != 0 || K > 32768 || ldx < K || r < 0 || r > 64 || !(eps > 0.0f)) return ZQFP_E_SHAPE;
+    if (M == 0) return ZQFP_OK;
+    if (!X || !gain || !bias || !Xq || !sx) return ZQFP_E_NULL;
+    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
+    if (!aligned16(X) || !aligned16(gain) || !aligned16(bias) || !aligned16(Xq) || (ldx % 8) != 0 ||
+        (r > 0 && !aligned16(U)))
+        return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
+                                             static_cast<const uint16_t*>(U), r, T, static_cast<const uint16_t*>(gain),
+                                             static_cast<const uint16_t*>(bias), eps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 

@@ -156,10 +156,11 @@ struct Lorc {
 };
 
 // Launchers (each enqueues on `s` and returns the launch status).
-// gain == nullptr: plain quantizer; else RMS normalisation (gain [K] bf16, eps) fused in front, K <= 32768
+// gain == nullptr: plain quantizer; gain only: RMS normalisation (gain [K] bf16, eps) fused in front;
+// gain and bias: layer normalisation.  Normalised rows: K <= 32768
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq,
-                               float* sx, const uint16_t* U, int r, float* T, const uint16_t* gain, float eps,
-                               hipStream_t s);
+                               float* sx, const uint16_t* U, int r, float* T, const uint16_t* gain,
+                               const uint16_t* bias, float eps, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t* W, int64_t ldw, const BlobLayout& L, int mode,
                               uint8_t* blob, hipStream_t s);
 hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* codes, uint8_t* exps,

@@ -57,6 +57,8 @@ def lib():
         L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p, p]
         L.zqfp_rmsnorm_quantize_act_fp8.restype = c.c_int
         L.zqfp_rmsnorm_quantize_act_fp8.argtypes = [p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_layernorm_quantize_act_fp8.restype = c.c_int
+        L.zqfp_layernorm_quantize_act_fp8.argtypes = [p, p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_probe_stream_read.restype = c.c_int
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
         L.zqfp_probe_mfma.restype = c.c_int
@@ -115,6 +117,24 @@ def rmsnorm_quantize_act_fp8(X, gain, eps, U=None):
         T = torch.empty((M, r), dtype=torch.float32, device=X.device)
     _check(lib().zqfp_rmsnorm_quantize_act_fp8(_ptr(X), _ptr(gain), float(eps), M, K, X.stride(0), _ptr(Xq), _ptr(sx),
                                                _ptr(U), r, _ptr(T), _stream(X)))
+    return (Xq, sx) if U is None else (Xq, sx, T)
+
+
+def layernorm_quantize_act_fp8(X, gain, bias, eps, U=None):
+    """Layer normalisation (gain, bias [K] bf16, eps > 0) fused in front of quantize_act_fp8; same outputs."""
+    _dev(X, torch.bfloat16, 2), _dev(gain, torch.bfloat16, 1), _dev(bias, torch.bfloat16, 1)
+    M, K = X.shape
+    if gain.shape[0] != K or bias.shape[0] != K:
+        raise ZqfpError(-2, "gain / bias length")
+    Xq = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    T, r = None, 0
+    if U is not None:
+        _dev(U, torch.float16, 2)
+        r = U.shape[1]
+        T = torch.empty((M, r), dtype=torch.float32, device=X.device)
+    _check(lib().zqfp_layernorm_quantize_act_fp8(_ptr(X), _ptr(gain), _ptr(bias), float(eps), M, K, X.stride(0), _ptr(Xq),
+                                                 _ptr(sx), _ptr(U), r, _ptr(T), _stream(X)))
     return (Xq, sx) if U is None else (Xq, sx, T)
 
 

@@ -361,6 +361,85 @@ def test_fused_rmsnorm_quantizer_argument_checks():
         zqfp.rmsnorm_quantize_act_fp8(X, g[:128].contiguous(), 1e-5)
 
 
+def _bias_bits(K):
+    rng = np.random.default_rng(4243)
+    return inputs.f32_to_bf16_bits((0.05 * rng.standard_normal(K)).astype(np.float32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,M,eps,shift", [("tiny", 16, 1e-5, 0.0), ("opt1p3b_fc1", 300, 1e-5, 0.25),
+                                              ("llama7b_qkv", 77, 1e-6, -3.0), ("llama13b_ffn_lorc", 16, 1e-5, 0.5),
+                                              ("llama70b_ffn_decode", 64, 1e-5, 0.0),
+                                              ("llama70b_ffn_decode", 130, 1e-2, 40.0),
+                                              # many tokens without LoRC: the wave-per-token kernel
+                                              ("opt1p3b_fc1", 1027, 1e-5, 1.0), ("llama7b_qkv", 1100, 1e-5, 0.0)])
+def test_fused_layernorm_quantizer_equals_the_unfused_sequence_bit_for_bit(name, M, eps, shift):
+    """Layer normalisation (gain and bias) fused in front of the quantizer: codes and scales are those of the
+    oracle's normalisation (bf16 result) followed by the oracle's quantizer; rows carry a common offset so that
+    the mean matters, one token is all zero (its normalised row is the bias) and one is constant (variance 0)."""
+    cfg = CFG[name]
+    X = inputs.make_x(cfg, M)
+    if shift:
+        rows = np.linspace(-shift, shift, M, dtype=np.float32).reshape(-1, 1)
+        X = inputs.f32_to_bf16_bits(inputs.bf16_bits_to_f32(X) + rows)
+    X[M // 2] = 0
+    X[M // 3] = inputs.f32_to_bf16_bits(np.full(cfg.K, 1.5, np.float32))
+    g, b = _gain_bits(cfg.K), _bias_bits(cfg.K)
+    Yn = oracle.layernorm_bf16(X, g, b, eps)
+    Xq_o, sx_o = oracle.quantize_act(Yn)
+    gd = bf16_tensor(g.reshape(1, -1)).reshape(-1).contiguous()
+    bd = bf16_tensor(b.reshape(1, -1)).reshape(-1).contiguous()
+    if cfg.rank:
+        U, _ = inputs.make_uv(cfg)
+        T_o, Tabs = oracle.lorc_left(Yn, U)
+        Xq, sx, T = zqfp.layernorm_quantize_act_fp8(bf16_tensor(X), gd, bd, eps, f16_tensor(U))
+        T = _sync_np(T)
+        assert np.all(np.abs(T - T_o) <= 2.0 ** -18 * Tabs + 1e-30)
+    else:
+        Xq, sx = zqfp.layernorm_quantize_act_fp8(bf16_tensor(X), gd, bd, eps)
+    Xq, sx = _sync_np(Xq), _sync_np(sx)
+    assert bits_equal_f32(sx, sx_o)
+    assert np.array_equal(Xq, Xq_o)
+    # all-zero and constant tokens normalise to the bias alone
+    Xq_b, sx_b = oracle.quantize_act(b.reshape(1, -1))
+    for m in (M // 2, M // 3):
+        assert np.array_equal(Xq[m], Xq_b[0]) and bits_equal_f32(sx[m:m + 1], sx_b)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K,M,rank", [(11008, 5, 0), (28672, 3, 8), (32768, 2, 0), (8320, 70, 8), (128, 9, 0)])
+def test_fused_normalisations_on_rows_beyond_the_register_budget_of_256_threads(K, M, rank):
+    """Rows of up to 32768 elements (the documented limit) and the shortest row, both normalisations."""
+    import dataclasses
+    cfg = dataclasses.replace(CFG["llama7b_qkv"], K=K, N=64, G=64, rank=rank, seed=K + M)
+    X = inputs.f32_to_bf16_bits(inputs.bf16_bits_to_f32(inputs.make_x(cfg, M)) + np.float32(0.75))
+    g, b = _gain_bits(K), _bias_bits(K)
+    gd = bf16_tensor(g.reshape(1, -1)).reshape(-1).contiguous()
+    bd = bf16_tensor(b.reshape(1, -1)).reshape(-1).contiguous()
+    U = inputs.make_uv(cfg)[0] if rank else None
+    Ud = f16_tensor(U) if rank else None
+    for Yn, out in ((oracle.rmsnorm_bf16(X, g, 1e-5), zqfp.rmsnorm_quantize_act_fp8(bf16_tensor(X), gd, 1e-5, Ud)),
+                    (oracle.layernorm_bf16(X, g, b, 1e-5),
+                     zqfp.layernorm_quantize_act_fp8(bf16_tensor(X), gd, bd, 1e-5, Ud))):
+        Xq_o, sx_o = oracle.quantize_act(Yn)
+        assert bits_equal_f32(_sync_np(out[1]), sx_o)
+        assert np.array_equal(_sync_np(out[0]), Xq_o)
+        if rank:
+            T_o, Tabs = oracle.lorc_left(Yn, U)
+            assert np.all(np.abs(_sync_np(out[2]) - T_o) <= 2.0 ** -18 * Tabs + 1e-30)
+
+
+@pytest.mark.gpu
+def test_fused_layernorm_quantizer_argument_checks():
+    X = bf16_tensor(inputs.make_x(CFG["tiny"], 4))
+    g = bf16_tensor(_gain_bits(256).reshape(1, -1)).reshape(-1).contiguous()
+    b = bf16_tensor(_bias_bits(256).reshape(1, -1)).reshape(-1).contiguous()
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.layernorm_quantize_act_fp8(X, g, b, 0.0)
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.layernorm_quantize_act_fp8(X, g, b[:128].contiguous(), 1e-5)
+
+
 def test_gemm_k_split_is_optional_and_agrees_with_the_unsplit_launch():
     """Without a workspace the same call runs un-split; both results meet the parity bar and the
     workspace query names a size exactly when a split is planned."""
