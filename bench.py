@@ -49,6 +49,24 @@ def algorithmic_bytes(cfg, M, out_bytes=4):
     return w + M * K + 4 * M + out_bytes * M * N + (4 * M * r + 2 * r * N if r else 0)
 
 
+def timed_replays(g, replays, settle_s=0.06):
+    """Milliseconds per replay of graph g, after replaying it untimed for `settle_s` seconds (clock settling)."""
+    t0 = time.perf_counter()
+    while True:
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        if time.perf_counter() - t0 >= settle_s:
+            break
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
+        g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / replays
+
+
 class Workload:
     def __init__(self, name, M, accum, copies=1):
         self.cfg = cfg = inputs.CONFIGS[name]
@@ -118,15 +136,7 @@ class Workload:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             launches()
-        g.replay()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(replays):
-            g.replay()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / (replays * len(self.packed))
+        return timed_replays(g, replays) / len(self.packed)
 
     def step_graph_ms(self, replays=20):
         """Average time of the whole step (quantizer + GEMM) with host launch gaps removed: one HIP
@@ -140,15 +150,7 @@ class Workload:
         with torch.cuda.graph(g):
             for _ in self.packed:
                 self.step()
-        g.replay()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(replays):
-            g.replay()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / (replays * len(self.packed))
+        return timed_replays(g, replays) / len(self.packed)
 
     def summary(self, steps, warmup):
         ms, gemm_ms = self.run(steps, warmup)
@@ -208,15 +210,7 @@ def quantizer_rows(name="llama7b_qkv", M=4096):
         with torch.cuda.graph(g):
             for x in Xs:
                 fn(x)
-        g.replay()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(5):
-            g.replay()
-        b.record()
-        torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / (5 * len(Xs))
+        ms = timed_replays(g, 5) / len(Xs)
         nbytes = 3 * M * cfg.K + 4 * M + {"q": 0, "r": 2 * cfg.K, "l": 4 * cfg.K}[label[0]]
         gbs = nbytes / (ms * 1e-3) / 1e9
         rows.append({"call": label, "workload": f"{M}x{cfg.K} bf16", "ms": round(ms, 5), "gbs": round(gbs, 1),
@@ -234,8 +228,9 @@ def measured_ceilings():
     wgs_mfma = 256
     fsink = torch.zeros(512 * wgs_mfma, dtype=torch.float32, device="cuda")
 
-    def timed(fn, reps):
-        fn()
+    def timed(fn, reps, warm):
+        for _ in range(warm):  # long enough for the clock to settle
+            fn()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
@@ -246,13 +241,13 @@ def measured_ceilings():
         return a.elapsed_time(b) / reps
 
     wgs_read = 2048
-    ms_read = timed(lambda: zqfp.probe_stream_read(src, sink, wgs_read), 5)
+    ms_read = timed(lambda: zqfp.probe_stream_read(src, sink, wgs_read), 20, 120)
     read_bytes = (src.numel() // (wgs_read * 4 * 8 * 1024)) * (wgs_read * 4 * 8 * 1024)
     iters = 4000
     flop = [0.0]
     def mf():
         flop[0] = zqfp.probe_mfma(ops, fsink, iters, wgs_mfma)
-    ms_mfma = timed(mf, 3)
+    ms_mfma = timed(mf, 10, 12)
     del src
     torch.cuda.empty_cache()
     return {"stream_read_gbs": round(read_bytes / (ms_read * 1e-3) / 1e9, 1),
@@ -285,8 +280,10 @@ def cpu_baseline(name, M, rows=4096):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # The GPU's clock takes some 50 ms of uninterrupted work to settle (launch times first rise, then fall
+    # below where they started); the default warm-up is sized so that the timed steps see the settled clock.
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="llama7b_qkv")
     ap.add_argument("--M", type=int, default=4096)
     ap.add_argument("--accum", choices=["exact", "fast"], default="exact")

@@ -11,11 +11,14 @@
 // matrix core, no unpack and no multiply).
 //
 // Two waves share a SIMD so that one wave's LDS reads and barrier waits hide
-// behind the other's matrix instructions.  LDS holds three stages.  A stage
+// behind the other's matrix instructions: two of an 8-wave workgroup that has
+// the compute unit to itself (three LDS stages), or one from each of two 4-wave
+// workgroups (two stages each), whose prologues, epilogues and barriers then
+// fall at different times.  A stage
 // is filled by LDS-direct loads (global_load_lds_dwordx4: every lane names a
 // 16 B chunk in global memory, the wave's 64 chunks land in one contiguous
-// 1 KB block of LDS), two k-steps ahead of its use: no staging registers, no
-// LDS store instructions, and two k-steps of slack for the memory latency.
+// 1 KB block of LDS), NSTAGE - 1 k-steps ahead of its use: no staging
+// registers, no LDS store instructions.
 // A stage keeps the activation tile as rows of 128 B with XOR-swizzled 16 B
 // chunks (whole cache lines on the way in, conflict-free 16 B/lane operand
 // reads on the way out); the weight tile already has its operand order in
@@ -99,14 +102,15 @@ __device__ inline void wait_loads_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE_>
 struct TileCfg {
     static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
     static constexpr int BM = WAVES_M * WTM * 16, BN = WAVES_N * WTN * 16;
     static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 64;
     static constexpr int E_BYTES = THREADS * 4;               // one exponent dword per output channel (first BN used)
     static constexpr int STAGE = A_BYTES + B_BYTES + E_BYTES;
-    static constexpr int NSTAGE = 3;
+    static constexpr int NSTAGE = NSTAGE_;
+    static_assert(NSTAGE == 2 || NSTAGE == 3, "the loop keeps one or two k-tiles in flight behind the one it multiplies");
     static constexpr int A_CHUNKS = A_BYTES / 16 / THREADS;  // 16 B chunks per thread
     static constexpr int B_CHUNKS = B_BYTES / 16 / THREADS;
     static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile / thread mismatch");
@@ -115,13 +119,13 @@ struct TileCfg {
 
 // Two waves per SIMD in every configuration (8-wave workgroups alone on a compute unit, 4-wave
 // workgroups in pairs): 256 registers per lane.
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, bool EXACT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
     BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n, int ksplit,
     int kslice, float* __restrict__ partial)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE>;
     constexpr int kThreads = C::THREADS;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     //   * behind the block's second instruction: the request for the next activation fragment
     //     (row block I + 1, or row block 0 of the next stage st_next when I is the last and NEXT);
     //   * last block only (it runs behind the step's barrier, see below): one per instruction, the
-    //     requests for k-tile kt + 3 into this step's stage (LOAD) and, behind the last instruction
+    //     requests for k-tile kt + NSTAGE into this step's stage (LOAD) and, behind the last instruction
     //     that reads them, the next step's weight fragments and exponent dwords (NEXT);
     //   * block 0: instruction j waits for its own fragment j only (read_b order: e0 b0 e1 b1 ...):
     //     2 (WTN - 1 - j) younger reads, plus the 2 of the activation request once that is out.
@@ -322,7 +326,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
                     constexpr int PER = (NSIDE + WTN * PASSES - 1) / (WTN * PASSES);  // loads per slot
 #pragma unroll
                     for (int q = 0; q < PER; ++q)
-                        if (LOAD && T * PER + q < NSIDE) side_load(T * PER + q, kt + 3, stage, cur_load);
+                        if (LOAD && T * PER + q < NSIDE) side_load(T * PER + q, kt + NSTAGE, stage, cur_load);
                     if constexpr (NEXT && P == PASSES - 1) {
                         e_cur[J] = lds_read4<J * 64>(e_addr + st_next);
                         bq[J] = lds_read16<J * 1024>(b_addr + st_next);
@@ -338,7 +342,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     auto next = [](int st) { return st == C::NSTAGE - 1 ? 0 : st + 1; };
     // row blocks 0 .. WTM - 2 of step kt, then the step's barrier.  It sits BEFORE the last row
     // block: by then every read of this stage has been issued (the last activation fragment is
-    // requested one block ahead), so behind the barrier the stage is free for k-tile kt + 3, and
+    // requested one block ahead), so behind the barrier the stage is free for k-tile kt + NSTAGE, and
     // the next stage is complete: each wave has waited for all of its loads but the WAIT that may
     // belong to k-tile kt + 2.
     auto head_blocks = [&](int kt, int stage, auto wait_tag) __attribute__((always_inline)) {
@@ -347,22 +351,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         wait_loads_then_barrier<decltype(wait_tag)::value>();
     };
 
-    // ---- prologue: k-tiles 0, 1 and 2 into stages 0, 1 and 2; the first operands into registers
+    // ---- prologue: k-tiles 0 .. NSTAGE - 1 into stages of the same number; the first operands into registers
 #pragma unroll
     for (int t = 0; t < NSIDE; ++t) side_load(t, 0, 0, cur_load);
     if (nkt > 1) {
         advance(cur_load);
 #pragma unroll
         for (int t = 0; t < NSIDE; ++t) side_load(t, 1, 1, cur_load);
+        if constexpr (NSTAGE == 2) advance(cur_load);  // now at k-tile 2
     }
-    if (nkt > 2) {
-        advance(cur_load);
+    if constexpr (NSTAGE == 3) {
+        if (nkt > 2) {
+            advance(cur_load);
 #pragma unroll
-        for (int t = 0; t < NSIDE; ++t) side_load(t, 2, 2, cur_load);
-        advance(cur_load);  // now at k-tile 3
+            for (int t = 0; t < NSIDE; ++t) side_load(t, 2, 2, cur_load);
+            advance(cur_load);  // now at k-tile 3
+        }
     }
     // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done
-    if (nkt > 2) wait_loads_then_barrier<2 * NSIDE>();
+    if (NSTAGE == 3 && nkt > 2) wait_loads_then_barrier<2 * NSIDE>();
     else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
     else wait_loads_then_barrier<0>();
     ta = lds_read16<0>(a_addr0);
@@ -379,19 +386,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         for (int d = 0; d < 8; ++d) split_in_place(fy, d);
     }
 
-    // ---- main loop.  Step kt computes stage kt % 3; k-tiles kt + 1 and kt + 2 are in the other two
-    // stages or on their way, k-tile kt + 3 is requested into stage kt % 3 behind the step's
-    // barrier, two steps of slack for the memory latency.  The loop is rotated so that no LDS read
-    // is in flight across its back edge: an iteration is the last row block of step kt followed by
-    // the first blocks of step kt + 1 and that step's barrier.  The last steps request nothing
-    // and are peeled.
-    using W1 = std::integral_constant<int, NSIDE>;
+    // ---- main loop.  Step kt computes stage kt % NSTAGE; the k-tiles behind it (kt + 1, and kt + 2 with
+    // three stages) are in the other stages or on their way, k-tile kt + NSTAGE is requested into
+    // stage kt % NSTAGE behind the step's barrier: two steps of slack for the memory latency with three
+    // stages, most of one with two (two workgroups then share a compute unit and fill each other's
+    // gaps).  The loop is rotated so that no LDS read is in flight across its back edge: an iteration is
+    // the last row block of step kt followed by the first blocks of step kt + 1 and that step's barrier,
+    // at which the loads of k-tile kt + 2 must have landed and only younger ones (three stages: those of
+    // k-tile kt + 3) may be outstanding.  The last steps request nothing and are peeled.
+    using W1 = std::integral_constant<int, (NSTAGE - 2) * NSIDE>;
     using W0 = std::integral_constant<int, 0>;
     int stage = 0;
     if (nkt > 2) head_blocks(0, 0, W1{});
     else head_blocks(0, 0, W0{});
     int kt = 0;
-    for (; kt + 3 < nkt; ++kt) {  // k-tiles kt + 2 and kt + 3 exist
+    for (; kt + NSTAGE < nkt; ++kt) {  // k-tile kt + NSTAGE exists
         row_block(std::integral_constant<int, WTM - 1>{}, kt, stage_off(stage), stage_off(next(stage)), stage, yes{}, yes{});
         advance(cur_comp);
         advance(cur_load);
@@ -548,16 +557,16 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
     }
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, bool EXACT>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                       void* Y, int64_t ldy, int out_dtype, int ksplit, int kslice, float* partial, hipStream_t s)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE>;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
     const int units = tiles_m * tiles_n * ksplit;
     const int per = (units + 7) / 8;
     const size_t smem = C::NSTAGE * C::STAGE;
-    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, EXACT>;
+    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, EXACT>;
     static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -579,9 +588,11 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
     TilePlan p = plan_tiles(M, L.Np, L.nkt);
     if (workspace == nullptr) { p.ksplit = 1; p.kslice = (int)L.nkt; }  // no room for partial tiles: one slice
     float* ws = static_cast<float*>(workspace);
-    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    return launch_cfg<2, 4, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
+    if (p.bm == 128 && p.bn == 256)
+        return launch_cfg<4, 8, 2, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    return launch_cfg<2, 4, 2, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
 }
 
 }  // namespace

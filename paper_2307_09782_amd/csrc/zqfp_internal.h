@@ -104,12 +104,14 @@ __device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i&
 }
 
 // Tile shape and K-split of the tiled GEMM for a problem size (the launcher and the workspace query
-// must agree).  256 x 256 tiles (8 waves, one workgroup per compute unit) once they fill the 256
-// compute units at least ~1.5 times, or three quarters of them in a single round; else 128 x 128
-// (4 waves, two workgroups per compute unit) if there are enough of those; else 64 x 128, which also
-// serves 16 < M <= 64, where the kernel is a weight stream.  When even those tiles fill less than a
-// third of the chip (few output channels, long K: down-projections at small M), K is cut into
-// `ksplit` slices of `kslice` k-tiles, each tile-slice goes to its own workgroup, and the float32
+// must agree).  Counted in 256 x 256 tiles: with at least ~1.5 per compute unit (256 of them) the
+// kernel runs 128 x 256 tiles, 4 waves and two LDS stages, two workgroups per compute unit that fill
+// each other's prologue, epilogue and barrier gaps; with three quarters to one per compute unit, one
+// round of 256 x 256 tiles (8 waves, three LDS stages, one workgroup per compute unit); else
+// 128 x 128 (4 waves, two workgroups per compute unit) if there are enough of those; else 64 x 128,
+// which also serves 16 < M <= 64, where the kernel is a weight stream.  When even those tiles fill
+// less than a third of the chip (few output channels, long K: down-projections at small M), K is cut
+// into `ksplit` slices of `kslice` k-tiles, each tile-slice goes to its own workgroup, and the float32
 // partial tiles meet in a workspace (ksplit * M * Np floats) that a second kernel sums in fixed order.
 struct TilePlan {
     int bm, bn;       // tile shape
@@ -122,7 +124,8 @@ inline TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((Np + bn - 1) / bn); };
     TilePlan p{64, 128, 1, (int)nkt};
     const int64_t n256 = tiles(256, 256);
-    if (n256 >= kCUs * 3 / 2 || (n256 <= kCUs && n256 * 4 >= kCUs * 3)) { p.bm = 256; p.bn = 256; return p; }
+    if (n256 >= kCUs * 3 / 2) { p.bm = 128; p.bn = 256; return p; }
+    if (n256 <= kCUs && n256 * 4 >= kCUs * 3) { p.bm = 256; p.bn = 256; return p; }
     if (M > 64 && tiles(128, 128) >= 384) { p.bm = 128; p.bn = 128; return p; }
     const int64_t slots = 2 * kCUs, nt = tiles(64, 128);
     int64_t want = slots / nt;
