@@ -71,6 +71,12 @@ def lib():
         L.orc_lorc_left.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int, p, p]
         L.orc_rmsnorm_bf16.restype = None
         L.orc_rmsnorm_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_float, p]
+        L.orc_add_bf16.restype = None
+        L.orc_add_bf16.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int64, c.c_int64, p]
+        L.orc_relu_bf16.restype = None
+        L.orc_relu_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p]
+        L.orc_swiglu_bf16.restype = None
+        L.orc_swiglu_bf16.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int64, c.c_int64, p]
         L.orc_layernorm_bf16.restype = None
         L.orc_layernorm_bf16.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, p, c.c_float, p]
         L.orc_max_threads.restype = c.c_int
@@ -148,6 +154,37 @@ def layernorm_bf16(X, g, b, eps):
         raise ValueError("gain / bias length or eps")
     Y = np.empty((M, K), np.uint16)
     lib().orc_layernorm_bf16(_ptr(X), M, K, K, _ptr(g), _ptr(b), float(eps), _ptr(Y))
+    return Y
+
+
+def add_bf16(X, R):
+    """h = bf16(x + r) on bf16 bits (one binary32 addition, round to nearest even)."""
+    _chk(X, np.uint16, 2), _chk(R, np.uint16, 2)
+    if X.shape != R.shape:
+        raise ValueError("shapes differ")
+    M, K = X.shape
+    H = np.empty((M, K), np.uint16)
+    lib().orc_add_bf16(_ptr(X), _ptr(R), M, K, K, K, _ptr(H))
+    return H
+
+
+def relu_bf16(X):
+    """y = x if x > 0 else +0, on bf16 bits."""
+    _chk(X, np.uint16, 2)
+    M, K = X.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().orc_relu_bf16(_ptr(X), M, K, K, _ptr(Y))
+    return Y
+
+
+def swiglu_bf16(G, U):
+    """y = bf16(silu(g) * u) on bf16 bits, evaluated in binary64."""
+    _chk(G, np.uint16, 2), _chk(U, np.uint16, 2)
+    if G.shape != U.shape:
+        raise ValueError("shapes differ")
+    M, K = G.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().orc_swiglu_bf16(_ptr(G), _ptr(U), M, K, K, K, _ptr(Y))
     return Y
 
 

@@ -22,6 +22,9 @@
  *                  an fp64 sum.
  *   rmsnorm,     : the normalisations whose output Section 3 quantizes (textbook
  *   layernorm      definitions; see orc_rmsnorm_bf16, orc_layernorm_bf16).
+ *   add, relu,   : the other producers of quantized activations (residual add in front
+ *   swiglu         of the normalisation; the ReLU in front of fc2, Section 3 "Distribution
+ *                  of Activations"; its gated counterpart in the LLaMA models of Section 4).
  *   lorc         : Section 3 (LoRC: the low-rank product U.V is added to the
  *                  quantized weight), Appendix A (rank 8 for LLaMA).
  *
@@ -312,6 +315,53 @@ void orc_layernorm_bf16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
             Y[m * K + k] = f32_to_bf16_bits_rne(e);
         }
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* other producers of the quantized activations                        */
+/* ------------------------------------------------------------------ */
+
+/* Residual stream in front of a normalisation: h = x + r, rounded to bfloat16 (what a stand-alone
+ * add kernel hands on, both to the normalisation and to the next residual connection).  One
+ * binary32 addition, then bfloat16 round-to-nearest-even.
+ * X, R: M x K bf16 bits, row strides ldx, ldr.  H: M x K bf16 bits, dense. */
+void orc_add_bf16(const uint16_t *X, const uint16_t *R, int64_t M, int64_t K,
+                  int64_t ldx, int64_t ldr, uint16_t *H)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float h = bf16_bits_to_f32(X[m * ldx + k]) + bf16_bits_to_f32(R[m * ldr + k]);
+            H[m * K + k] = f32_to_bf16_bits_rne(h);
+        }
+}
+
+/* The input of fc2 is the output of a ReLU (Section 3, "Distribution of Activations", observation
+ * (2): negative values are voided, positive values pass unmodified).  y = x if x > 0, else +0.
+ * X: M x K bf16 bits, row stride ldx.  Y: M x K bf16 bits, dense. */
+void orc_relu_bf16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, uint16_t *Y)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            uint16_t x = X[m * ldx + k];
+            Y[m * K + k] = bf16_bits_to_f32(x) > 0.0f ? x : 0;
+        }
+}
+
+/* The LLaMA counterpart of that producer (the models of Section 4 gate their feed-forward layer):
+ * the input of the down projection is silu(g) * u with silu(g) = g / (1 + exp(-g)).  Evaluated in
+ * binary64 (library exp), then rounded to binary32 and from there to bfloat16:
+ *     t = g / (1 + exp(-g)) * u;  y = bf16_rne(fl32(t)).
+ * G, U: M x K bf16 bits, row strides ldg, ldu.  Y: M x K bf16 bits, dense. */
+void orc_swiglu_bf16(const uint16_t *G, const uint16_t *U, int64_t M, int64_t K,
+                     int64_t ldg, int64_t ldu, uint16_t *Y)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            double g = (double)bf16_bits_to_f32(G[m * ldg + k]);
+            double u = (double)bf16_bits_to_f32(U[m * ldu + k]);
+            double t = g / (1.0 + exp(-g)) * u;
+            Y[m * K + k] = f32_to_bf16_bits_rne((float)t);
+        }
 }
 
 /* ------------------------------------------------------------------ */
