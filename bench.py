@@ -191,30 +191,42 @@ def calibration_copy(nbytes=1 << 30):
 
 
 def quantizer_rows(name="llama7b_qkv", M=4096):
-    """The quantizer alone and fused behind RMS or layer normalisation, HBM-bound (2 B read + 1 B written per
-    element): one HIP graph of calls rotating through input copies that exceed the last-level cache."""
+    """The quantizer alone and behind its fused producers, HBM-bound (2 B read + 1 B written per element, plus
+    what the producer reads and writes): one HIP graph of calls rotating through input copies that exceed the
+    last-level cache."""
     cfg = inputs.CONFIGS[name]
+    K = cfg.K
     X = bf16_dev(inputs.make_x(cfg, M))
-    copies = max(1, -(-600_000_000 // (2 * M * cfg.K)))
+    copies = max(1, -(-600_000_000 // (2 * M * K)))
     Xs = [X] + [X.clone() for _ in range(copies - 1)]
-    gain = torch.ones(cfg.K, dtype=torch.bfloat16, device="cuda")
-    bias = torch.zeros(cfg.K, dtype=torch.bfloat16, device="cuda")
+    gain = torch.ones(K, dtype=torch.bfloat16, device="cuda")
+    bias = torch.zeros(K, dtype=torch.bfloat16, device="cuda")
+    H = torch.empty_like(X)
+    # the gated feed-forward input of the same model: 11008 channels, gate and up halves of one tensor
+    Kf = inputs.CONFIGS["llama7b_ffn_up"].N
+    GU = torch.randn((M, 2 * Kf), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    GUs = [GU] + [GU.clone() for _ in range(max(1, -(-600_000_000 // (4 * M * Kf))) - 1)]
     rows = []
-    for label, fn in (("quantize_act_fp8", lambda x: zqfp.quantize_act_fp8(x)),
-                      ("rmsnorm_quantize_act_fp8", lambda x: zqfp.rmsnorm_quantize_act_fp8(x, gain, 1e-5)),
-                      ("layernorm_quantize_act_fp8", lambda x: zqfp.layernorm_quantize_act_fp8(x, gain, bias, 1e-5))):
-        for x in Xs[:2]:
+    for label, fn, ins, kk, nbytes in (
+            ("quantize_act_fp8", lambda x: zqfp.quantize_act_fp8(x), Xs, K, 3 * M * K),
+            ("rmsnorm_quantize_act_fp8", lambda x: zqfp.rmsnorm_quantize_act_fp8(x, gain, 1e-5), Xs, K, 3 * M * K + 2 * K),
+            ("layernorm_quantize_act_fp8", lambda x: zqfp.layernorm_quantize_act_fp8(x, gain, bias, 1e-5), Xs, K,
+             3 * M * K + 4 * K),
+            ("add_rmsnorm_quantize_act_fp8", lambda xr: zqfp.add_norm_quantize_act_fp8(xr[0], xr[1], gain, 1e-5, H=H),
+             list(zip(Xs, Xs[1:] + Xs[:1])), K, 7 * M * K + 2 * K),
+            ("relu_quantize_act_fp8", lambda x: zqfp.relu_quantize_act_fp8(x), Xs, K, 3 * M * K),
+            ("swiglu_quantize_act_fp8", lambda gu: zqfp.swiglu_quantize_act_fp8(gu[:, :Kf], gu[:, Kf:]), GUs, Kf, 5 * M * Kf)):
+        for x in ins[:2]:
             fn(x)
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for x in Xs:
+            for x in ins:
                 fn(x)
-        ms = timed_replays(g, 5) / len(Xs)
-        nbytes = 3 * M * cfg.K + 4 * M + {"q": 0, "r": 2 * cfg.K, "l": 4 * cfg.K}[label[0]]
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        rows.append({"call": label, "workload": f"{M}x{cfg.K} bf16", "ms": round(ms, 5), "gbs": round(gbs, 1),
-                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "input_copies_rotated": len(Xs)})
+        ms = timed_replays(g, 5) / len(ins)
+        gbs = (nbytes + 4 * M) / (ms * 1e-3) / 1e9
+        rows.append({"call": label, "workload": f"{M}x{kk} bf16", "ms": round(ms, 5), "gbs": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "input_copies_rotated": len(ins)})
     return rows
 
 

@@ -147,6 +147,61 @@ int zqfp_layernorm_quantize_act_fp8(const void *X, const void *gain,
                                     void *stream);
 
 /*
+ * add_rmsnorm_quantize_act_fp8, add_layernorm_quantize_act_fp8 -- the two
+ * calls above with the residual connection in front of the normalisation taken
+ * along:  h = bf16(X + R) (one binary32 addition, round to nearest even) is
+ * written to H and is what gets normalised and quantized.
+ *
+ *   R    [M, K] bfloat16, row stride ldr >= K (multiple of 8), 16-byte aligned  (in)
+ *   H    [M, K] bfloat16, dense, 16-byte aligned; may be R itself when
+ *        ldr == K (the residual stream updated in place), must not overlap
+ *        X or R otherwise                                                      (out)
+ * Other arguments, limits and errors as for the calls without the residual.
+ */
+int zqfp_add_rmsnorm_quantize_act_fp8(const void *X, const void *R, int64_t ldr,
+                                      void *H, const void *gain, float eps,
+                                      int64_t M, int64_t K, int64_t ldx,
+                                      uint8_t *Xq, float *sx,
+                                      const void *U, int r, float *T,
+                                      void *stream);
+int zqfp_add_layernorm_quantize_act_fp8(const void *X, const void *R,
+                                        int64_t ldr, void *H, const void *gain,
+                                        const void *bias, float eps,
+                                        int64_t M, int64_t K, int64_t ldx,
+                                        uint8_t *Xq, float *sx,
+                                        const void *U, int r, float *T,
+                                        void *stream);
+
+/*
+ * relu_quantize_act_fp8 -- the quantizer behind the ReLU whose output is the
+ * input of fc2 (paper Section 3, "Distribution of Activations", observation
+ * (2)):  y = X where X > 0, +0 elsewhere; then zqfp_quantize_act_fp8 on y.
+ * K <= 32768; other arguments and errors as for zqfp_quantize_act_fp8 (T = y.U).
+ */
+int zqfp_relu_quantize_act_fp8(const void *X, int64_t M, int64_t K, int64_t ldx,
+                               uint8_t *Xq, float *sx,
+                               const void *U, int r, float *T, void *stream);
+
+/*
+ * swiglu_quantize_act_fp8 -- the same for the gated feed-forward layer of the
+ * LLaMA models of paper Section 4, whose down projection reads
+ *
+ *   y[m,k] = bf16( silu(G[m,k]) * Up[m,k] ),   silu(g) = g / (1 + exp(-g)),
+ *
+ * evaluated in binary64, rounded to binary32 and from there to bfloat16; then
+ * zqfp_quantize_act_fp8 on y.
+ *
+ *   G    [M, K] bfloat16, row stride ldg (the gate projection's output)  (in)
+ *   Up   [M, K] bfloat16, row stride ldu (the up projection's output)    (in)
+ * K <= 32768; alignment, other arguments and errors as for
+ * zqfp_quantize_act_fp8 (T = y.U).
+ */
+int zqfp_swiglu_quantize_act_fp8(const void *G, const void *Up, int64_t ldu,
+                                 int64_t M, int64_t K, int64_t ldg,
+                                 uint8_t *Xq, float *sx,
+                                 const void *U, int r, float *T, void *stream);
+
+/*
  * pack_weight_fp4 -- group-wise FP4 (E2M1) weight quantization with
  * power-of-two scales (paper Section 3: fine-grained quantization; "Casting
  * the FP4 to FP8": S = 2^n with methods M1 / M2; Appendix A: group size).

@@ -126,6 +126,42 @@ __device__ inline uint4 normalize8_affine(uint4 v, uint4 g, uint4 b, float mu, f
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// 8 bf16 + 8 bf16 -> 8 bf16: one binary32 addition each, rounded to bf16
+__device__ inline uint4 add8(uint4 x, uint4 r)
+{
+    uint32_t xw[4] = {x.x, x.y, x.z, x.w}, rw[4] = {r.x, r.y, r.z, r.w}, o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] = f32_to_bf16_rne(bf16_lo(xw[i]) + bf16_lo(rw[i])) | (f32_to_bf16_rne(bf16_hi(xw[i]) + bf16_hi(rw[i])) << 16);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// ReLU on 8 bf16: a value passes unmodified if it is greater than zero, anything else becomes +0
+__device__ inline uint4 relu8(uint4 x)
+{
+    uint32_t w[4] = {x.x, x.y, x.z, x.w}, o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] = (bf16_lo(w[i]) > 0.0f ? (w[i] & 0xFFFFu) : 0u) | (bf16_hi(w[i]) > 0.0f ? (w[i] & 0xFFFF0000u) : 0u);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// silu(g) * u in binary64 (g / (1 + exp(-g)) * u), rounded to binary32 and from there to bf16
+__device__ inline uint32_t swiglu1(float g, float u)
+{
+    const double gd = (double)g;
+    const double t = gd / (1.0 + exp(-gd)) * (double)u;
+    return f32_to_bf16_rne((float)t);
+}
+__device__ inline uint4 swiglu8(uint4 g, uint4 u)
+{
+    uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w}, o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] = swiglu1(bf16_lo(gw[i]), bf16_lo(uw[i])) | (swiglu1(bf16_hi(gw[i]), bf16_hi(uw[i])) << 16);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 __device__ inline double sum_values(double acc, uint4 v)
 {
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -165,14 +201,19 @@ __device__ inline double sum_squares(double acc, uint4 v)
     return acc;
 }
 
-// NORM: 0 plain quantizer, 1 RMS normalisation (gain) in front, 2 layer normalisation (gain, bias) in front
+// NORM (the producer fused in front): 0 plain quantizer, 1 RMS normalisation (gain), 2 layer normalisation
+// (gain, bias), 3 ReLU, 4 gated SiLU (X is the gate, `other` the second operand).  With 1 and 2 a non-null
+// `other` is a residual added to X first; the sum, rounded to bf16, also goes to H.  Every thread reads an
+// element of `other` before it writes the same element of H, and nothing else touches it: H may be `other`.
 template <int RP, int NT, int NORM>
 __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict__ X, int64_t K, int64_t ldx,
                                                          uint8_t* __restrict__ Xq, float* __restrict__ sx,
                                                          const uint16_t* __restrict__ U, int r, float* __restrict__ T,
-                                                         const uint16_t* __restrict__ gain,
-                                                         const uint16_t* __restrict__ bias, float eps)
+                                                         Producer pr)
 {
+    const uint16_t* __restrict__ gain = pr.gain;
+    const uint16_t* __restrict__ bias = pr.bias;
+    const float eps = pr.eps;
     constexpr int kThreads = NT, kWaves = NT / 64;
     __shared__ uint32_t s_amax[kWaves];
     __shared__ float s_t[kWaves][RP > 0 ? RP : 1];
@@ -190,7 +231,29 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
         v[c] = make_uint4(0, 0, 0, 0);
         if (idx < nchunk) v[c] = xrow[idx];
     }
-    if constexpr (NORM != 0) {
+    if constexpr (NORM != 0) {  // the whole row sits in registers (the launcher guarantees K <= 8 * kRegChunks * NT)
+        if (pr.other != nullptr || NORM == 4) {
+            const uint4* orow = reinterpret_cast<const uint4*>(pr.other + row * pr.ld_other);
+            uint4* hrow = reinterpret_cast<uint4*>(pr.H + row * K);
+#pragma unroll
+            for (int c = 0; c < kRegChunks; ++c) {
+                const int idx = tid + c * kThreads;
+                if (idx < nchunk) {
+                    if constexpr (NORM == 4) {
+                        v[c] = swiglu8(v[c], orow[idx]);
+                    } else {
+                        v[c] = add8(v[c], orow[idx]);
+                        hrow[idx] = v[c];
+                    }
+                }
+            }
+        }
+        if constexpr (NORM == 3) {
+#pragma unroll
+            for (int c = 0; c < kRegChunks; ++c) v[c] = relu8(v[c]);
+        }
+    }
+    if constexpr (NORM == 1 || NORM == 2) {
         // the whole row sits in registers (the launcher guarantees K <= 8 * kRegChunks * NT): sum of
         // squares (and of the values, for layer normalisation) in binary64, waves meet in LDS and
         // every thread adds the partial sums in the same order; then the normalised row replaces the row
@@ -322,9 +385,11 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
 template <int MAXC, int NORM>
 __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
                                                      uint8_t* __restrict__ Xq, float* __restrict__ sx,
-                                                     const uint16_t* __restrict__ gain,
-                                                     const uint16_t* __restrict__ bias, float eps)
+                                                     Producer pr)
 {
+    const uint16_t* __restrict__ gain = pr.gain;
+    const uint16_t* __restrict__ bias = pr.bias;
+    const float eps = pr.eps;
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= M) return;  // whole waves leave; nothing below synchronises across waves
@@ -340,6 +405,28 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
         if (idx < nchunk) v[c] = xrow[idx];
     }
     if constexpr (NORM != 0) {
+        if (pr.other != nullptr || NORM == 4) {
+            const uint4* orow = reinterpret_cast<const uint4*>(pr.other + row * pr.ld_other);
+            uint4* hrow = reinterpret_cast<uint4*>(pr.H + row * K);
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c) {
+                const int idx = c * 64 + lane;
+                if (idx < nchunk) {
+                    if constexpr (NORM == 4) {
+                        v[c] = swiglu8(v[c], orow[idx]);
+                    } else {
+                        v[c] = add8(v[c], orow[idx]);
+                        hrow[idx] = v[c];
+                    }
+                }
+            }
+        }
+        if constexpr (NORM == 3) {
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c) v[c] = relu8(v[c]);
+        }
+    }
+    if constexpr (NORM == 1 || NORM == 2) {
         double ss = 0.0, s1 = 0.0;
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
@@ -386,20 +473,23 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
 }  // namespace
 
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx,
-                               const uint16_t* U, int r, float* T, const uint16_t* gain, const uint16_t* bias, float eps,
-                               hipStream_t s)
+                               const uint16_t* U, int r, float* T, const Producer& pr, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
-    const int norm = gain == nullptr ? 0 : bias == nullptr ? 1 : 2;
+    const int kind = pr.kind;
     if (r == 0 && M >= 1024 && K <= 8192) {  // many tokens, no LoRC factor: one wave per token
         const dim3 g4((unsigned)((M + 3) / 4));
-#define ZQ_ROWS_N(MAXC, NORM) \
-    hipLaunchKernelGGL((k_quantize_rows<MAXC, NORM>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, gain, bias, eps)
+#define ZQ_ROWS_N(MAXC, KIND) \
+    hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, pr)
 #define ZQ_ROWS(MAXC)                          \
     do {                                       \
-        if (norm == 2) ZQ_ROWS_N(MAXC, 2);     \
-        else if (norm == 1) ZQ_ROWS_N(MAXC, 1); \
-        else ZQ_ROWS_N(MAXC, 0);               \
+        switch (kind) {                        \
+        case 1: ZQ_ROWS_N(MAXC, 1); break;     \
+        case 2: ZQ_ROWS_N(MAXC, 2); break;     \
+        case 3: ZQ_ROWS_N(MAXC, 3); break;     \
+        case 4: ZQ_ROWS_N(MAXC, 4); break;     \
+        default: ZQ_ROWS_N(MAXC, 0); break;    \
+        }                                      \
     } while (0)
         if (K <= 2048) ZQ_ROWS(4);
         else if (K <= 4096) ZQ_ROWS(8);
@@ -409,21 +499,24 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
         return hipGetLastError();
     }
     const dim3 grid((unsigned)M);
-    // 1024 threads per token for a handful of tokens, and for normalised rows too long for 256 threads' registers
-    const bool wide = (M <= 64 && K >= 2048) || (norm != 0 && K > 8 * kRegChunks * 256);
-#define ZQ_QUANT_N(RP, NT, NORM) \
-    hipLaunchKernelGGL((k_quantize_act<RP, NT, NORM>), grid, dim3(NT), 0, s, X, K, ldx, Xq, sx, U, r, T, gain, bias, eps)
-#define ZQ_QUANT(RP)                                      \
-    do {                                                  \
-        if (wide) {                                       \
-            if (norm == 2) ZQ_QUANT_N(RP, 1024, 2);       \
-            else if (norm == 1) ZQ_QUANT_N(RP, 1024, 1);  \
-            else ZQ_QUANT_N(RP, 1024, 0);                 \
-        } else {                                          \
-            if (norm == 2) ZQ_QUANT_N(RP, 256, 2);        \
-            else if (norm == 1) ZQ_QUANT_N(RP, 256, 1);   \
-            else ZQ_QUANT_N(RP, 256, 0);                  \
-        }                                                 \
+    // 1024 threads per token for a handful of tokens, and for rows with a producer too long for 256 threads' registers
+    const bool wide = (M <= 64 && K >= 2048) || (kind != 0 && K > 8 * kRegChunks * 256);
+#define ZQ_QUANT_N(RP, NT, KIND) \
+    hipLaunchKernelGGL((k_quantize_act<RP, NT, KIND>), grid, dim3(NT), 0, s, X, K, ldx, Xq, sx, U, r, T, pr)
+#define ZQ_QUANT_K(RP, NT)                        \
+    do {                                          \
+        switch (kind) {                           \
+        case 1: ZQ_QUANT_N(RP, NT, 1); break;     \
+        case 2: ZQ_QUANT_N(RP, NT, 2); break;     \
+        case 3: ZQ_QUANT_N(RP, NT, 3); break;     \
+        case 4: ZQ_QUANT_N(RP, NT, 4); break;     \
+        default: ZQ_QUANT_N(RP, NT, 0); break;    \
+        }                                         \
+    } while (0)
+#define ZQ_QUANT(RP)                    \
+    do {                                \
+        if (wide) ZQ_QUANT_K(RP, 1024); \
+        else ZQ_QUANT_K(RP, 256);       \
     } while (0)
     if (r == 0) ZQ_QUANT(0);
     else if (r <= 8) ZQ_QUANT(8);
@@ -431,6 +524,7 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
     else if (r <= 32) ZQ_QUANT(32);
     else ZQ_QUANT(64);
 #undef ZQ_QUANT
+#undef ZQ_QUANT_K
 #undef ZQ_QUANT_N
     return hipGetLastError();
 }

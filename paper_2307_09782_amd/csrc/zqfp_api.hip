@@ -48,52 +48,81 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
 
 extern "C" {
 
-int zqfp_version(void) { return 102; }
+int zqfp_version(void) { return 103; }
 
 const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
+
+// argument checks shared by the quantizer entry points; `normalised` rows are limited to what registers hold
+static int quantize_common(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r,
+                           float* T, const zqfp::Producer& pr, void* stream)
+{
+    if (M < 0 || K <= 0 || K % 128 != 0 || ldx < K || r < 0 || r > 64) return ZQFP_E_SHAPE;
+    if (pr.kind != 0 && K > 32768) return ZQFP_E_SHAPE;
+    if ((pr.kind == 1 || pr.kind == 2) && !(pr.eps > 0.0f)) return ZQFP_E_SHAPE;
+    if (pr.other != nullptr && pr.ld_other < K) return ZQFP_E_SHAPE;
+    if (M == 0) return ZQFP_OK;
+    if (!X || !Xq || !sx) return ZQFP_E_NULL;
+    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
+    if ((pr.kind == 1 || pr.kind == 2) && !pr.gain) return ZQFP_E_NULL;
+    if (pr.kind == 2 && !pr.bias) return ZQFP_E_NULL;
+    if (pr.kind == 4 && !pr.other) return ZQFP_E_NULL;
+    if ((pr.kind == 1 || pr.kind == 2) && pr.other != nullptr && !pr.H) return ZQFP_E_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
+    if (!aligned16(pr.gain) || !aligned16(pr.bias) || !aligned16(pr.other) || !aligned16(pr.H) || (pr.ld_other % 8) != 0)
+        return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
+                                             static_cast<const uint16_t*>(U), r, T, pr, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+static const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
 
 int zqfp_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U,
                           int r, float* T, void* stream)
 {
-    if (M < 0 || K <= 0 || K % 128 != 0 || ldx < K || r < 0 || r > 64) return ZQFP_E_SHAPE;
-    if (M == 0) return ZQFP_OK;
-    if (!X || !Xq || !sx) return ZQFP_E_NULL;
-    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
-    if (!aligned16(X) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
-    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
-                                             static_cast<const uint16_t*>(U), r, T, nullptr, nullptr, 0.0f,
-                                             static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{0, nullptr, nullptr, nullptr, 0, nullptr, 0.0f}, stream);
 }
 
 int zqfp_rmsnorm_quantize_act_fp8(const void* X, const void* gain, float eps, int64_t M, int64_t K, int64_t ldx,
                                   uint8_t* Xq, float* sx, const void* U, int r, float* T, void* stream)
 {
-    if (M < 0 || K <= 0 || K % 128 != 0 || K > 32768 || ldx < K || r < 0 || r > 64 || !(eps > 0.0f)) return ZQFP_E_SHAPE;
-    if (M == 0) return ZQFP_OK;
-    if (!X || !gain || !Xq || !sx) return ZQFP_E_NULL;
-    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
-    if (!aligned16(X) || !aligned16(gain) || !aligned16(Xq) || (ldx % 8) != 0 || (r > 0 && !aligned16(U))) return ZQFP_E_ALIGN;
-    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
-                                             static_cast<const uint16_t*>(U), r, T, static_cast<const uint16_t*>(gain), nullptr,
-                                             eps, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{1, u16(gain), nullptr, nullptr, 0, nullptr, eps}, stream);
 }
 
 int zqfp_layernorm_quantize_act_fp8(const void* X, const void* gain, const void* bias, float eps, int64_t M, int64_t K,
                                     int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r, float* T, void* stream)
 {
-    if (M < 0 || K <= 0 || K % 128 != 0 || K > 32768 || ldx < K || r < 0 || r > 64 || !(eps > 0.0f)) return ZQFP_E_SHAPE;
-    if (M == 0) return ZQFP_OK;
-    if (!X || !gain || !bias || !Xq || !sx) return ZQFP_E_NULL;
-    if ((U != nullptr) != (r > 0) || (r > 0 && !T)) return ZQFP_E_NULL;
-    if (!aligned16(X) || !aligned16(gain) || !aligned16(bias) || !aligned16(Xq) || (ldx % 8) != 0 ||
-        (r > 0 && !aligned16(U)))
-        return ZQFP_E_ALIGN;
-    hipError_t e = zqfp::launch_quantize_act(static_cast<const uint16_t*>(X), M, K, ldx, Xq, sx,
-                                             static_cast<const uint16_t*>(U), r, T, static_cast<const uint16_t*>(gain),
-                                             static_cast<const uint16_t*>(bias), eps, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{2, u16(gain), u16(bias), nullptr, 0, nullptr, eps}, stream);
+}
+
+int zqfp_add_rmsnorm_quantize_act_fp8(const void* X, const void* R, int64_t ldr, void* H, const void* gain, float eps,
+                                      int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r,
+                                      float* T, void* stream)
+{
+    if (!R && M > 0) return ZQFP_E_NULL;
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T,
+                           zqfp::Producer{1, u16(gain), nullptr, u16(R), ldr, static_cast<uint16_t*>(H), eps}, stream);
+}
+
+int zqfp_add_layernorm_quantize_act_fp8(const void* X, const void* R, int64_t ldr, void* H, const void* gain,
+                                        const void* bias, float eps, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq,
+                                        float* sx, const void* U, int r, float* T, void* stream)
+{
+    if (!R && M > 0) return ZQFP_E_NULL;
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T,
+                           zqfp::Producer{2, u16(gain), u16(bias), u16(R), ldr, static_cast<uint16_t*>(H), eps}, stream);
+}
+
+int zqfp_relu_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U,
+                               int r, float* T, void* stream)
+{
+    return quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{3, nullptr, nullptr, nullptr, 0, nullptr, 0.0f}, stream);
+}
+
+int zqfp_swiglu_quantize_act_fp8(const void* G, const void* Up, int64_t ldu, int64_t M, int64_t K, int64_t ldg,
+                                 uint8_t* Xq, float* sx, const void* U, int r, float* T, void* stream)
+{
+    return quantize_common(G, M, K, ldg, Xq, sx, U, r, T, zqfp::Producer{4, nullptr, nullptr, u16(Up), ldu, nullptr, 0.0f}, stream);
 }
 
 size_t zqfp_packed_weight_bytes(int64_t K, int64_t N, int G)

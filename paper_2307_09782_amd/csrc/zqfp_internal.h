@@ -159,11 +159,18 @@ struct Lorc {
 };
 
 // Launchers (each enqueues on `s` and returns the launch status).
-// gain == nullptr: plain quantizer; gain only: RMS normalisation (gain [K] bf16, eps) fused in front;
-// gain and bias: layer normalisation.  Normalised rows: K <= 32768
+// What is fused in front of the activation quantizer (rows with a producer: K <= 32768).
+struct Producer {
+    int kind;               // 0 none, 1 RMS normalisation, 2 layer normalisation, 3 ReLU, 4 gated SiLU
+    const uint16_t* gain;   // [K] bf16 (kinds 1, 2)
+    const uint16_t* bias;   // [K] bf16 (kind 2)
+    const uint16_t* other;  // [M, K] bf16, row stride ld_other: residual added first (kinds 1, 2; may be null),
+    int64_t ld_other;       //   or the operand multiplied with silu(X) (kind 4)
+    uint16_t* H;            // [M, K] bf16 dense: X + other rounded to bf16 (kinds 1, 2 with a residual)
+    float eps;              // kinds 1, 2
+};
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq,
-                               float* sx, const uint16_t* U, int r, float* T, const uint16_t* gain,
-                               const uint16_t* bias, float eps, hipStream_t s);
+                               float* sx, const uint16_t* U, int r, float* T, const Producer& pr, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t* W, int64_t ldw, const BlobLayout& L, int mode,
                               uint8_t* blob, hipStream_t s);
 hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* codes, uint8_t* exps,

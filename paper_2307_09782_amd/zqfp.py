@@ -59,6 +59,14 @@ def lib():
         L.zqfp_rmsnorm_quantize_act_fp8.argtypes = [p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_layernorm_quantize_act_fp8.restype = c.c_int
         L.zqfp_layernorm_quantize_act_fp8.argtypes = [p, p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_add_rmsnorm_quantize_act_fp8.restype = c.c_int
+        L.zqfp_add_rmsnorm_quantize_act_fp8.argtypes = [p, p, i64, p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_add_layernorm_quantize_act_fp8.restype = c.c_int
+        L.zqfp_add_layernorm_quantize_act_fp8.argtypes = [p, p, i64, p, p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_relu_quantize_act_fp8.restype = c.c_int
+        L.zqfp_relu_quantize_act_fp8.argtypes = [p, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_swiglu_quantize_act_fp8.restype = c.c_int
+        L.zqfp_swiglu_quantize_act_fp8.argtypes = [p, p, i64, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_probe_stream_read.restype = c.c_int
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
         L.zqfp_probe_mfma.restype = c.c_int
@@ -83,6 +91,13 @@ def _stream(t):
 def _dev(t, dtype, ndim):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == ndim and t.is_contiguous()):
         raise TypeError(f"expected a contiguous CUDA tensor of dtype {dtype} and {ndim} dims")
+    return t
+
+
+def _rows(t, dtype):
+    """A 2-D CUDA tensor whose rows are contiguous (the row stride may exceed the row length)."""
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == 2 and t.stride(1) == 1):
+        raise TypeError(f"expected a 2-D CUDA tensor of dtype {dtype} with contiguous rows")
     return t
 
 
@@ -135,6 +150,62 @@ def layernorm_quantize_act_fp8(X, gain, bias, eps, U=None):
         T = torch.empty((M, r), dtype=torch.float32, device=X.device)
     _check(lib().zqfp_layernorm_quantize_act_fp8(_ptr(X), _ptr(gain), _ptr(bias), float(eps), M, K, X.stride(0), _ptr(Xq),
                                                  _ptr(sx), _ptr(U), r, _ptr(T), _stream(X)))
+    return (Xq, sx) if U is None else (Xq, sx, T)
+
+
+def _quant_outputs(X, U):
+    M, K = X.shape
+    Xq = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    T, r = None, 0
+    if U is not None:
+        _dev(U, torch.float16, 2)
+        r = U.shape[1]
+        T = torch.empty((M, r), dtype=torch.float32, device=X.device)
+    return Xq, sx, T, r
+
+
+def add_norm_quantize_act_fp8(X, R, gain, eps, bias=None, U=None, H=None):
+    """h = bf16(X + R), then RMS (bias None) or layer normalisation and the quantizer.  Returns (H, Xq, sx[, T]);
+    pass H=R to update the residual stream in place."""
+    _rows(X, torch.bfloat16), _rows(R, torch.bfloat16), _dev(gain, torch.bfloat16, 1)
+    M, K = X.shape
+    if tuple(R.shape) != (M, K) or gain.shape[0] != K or (bias is not None and bias.shape[0] != K):
+        raise ZqfpError(-2, "residual / gain / bias shape")
+    if H is None:
+        H = torch.empty((M, K), dtype=torch.bfloat16, device=X.device)
+    if tuple(H.shape) != (M, K) or not H.is_contiguous():
+        raise ZqfpError(-2, "H must be a dense [M, K] tensor")
+    Xq, sx, T, r = _quant_outputs(X, U)
+    if bias is None:
+        _check(lib().zqfp_add_rmsnorm_quantize_act_fp8(_ptr(X), _ptr(R), R.stride(0), _ptr(H), _ptr(gain), float(eps), M, K,
+                                                       X.stride(0), _ptr(Xq), _ptr(sx), _ptr(U), r, _ptr(T), _stream(X)))
+    else:
+        _dev(bias, torch.bfloat16, 1)
+        _check(lib().zqfp_add_layernorm_quantize_act_fp8(_ptr(X), _ptr(R), R.stride(0), _ptr(H), _ptr(gain), _ptr(bias),
+                                                         float(eps), M, K, X.stride(0), _ptr(Xq), _ptr(sx), _ptr(U), r,
+                                                         _ptr(T), _stream(X)))
+    return (H, Xq, sx) if U is None else (H, Xq, sx, T)
+
+
+def relu_quantize_act_fp8(X, U=None):
+    """ReLU fused in front of quantize_act_fp8; same outputs."""
+    _rows(X, torch.bfloat16)
+    M, K = X.shape
+    Xq, sx, T, r = _quant_outputs(X, U)
+    _check(lib().zqfp_relu_quantize_act_fp8(_ptr(X), M, K, X.stride(0), _ptr(Xq), _ptr(sx), _ptr(U), r, _ptr(T), _stream(X)))
+    return (Xq, sx) if U is None else (Xq, sx, T)
+
+
+def swiglu_quantize_act_fp8(G, Up, U=None):
+    """bf16(silu(G) * Up) fused in front of quantize_act_fp8; same outputs."""
+    _rows(G, torch.bfloat16), _rows(Up, torch.bfloat16)
+    M, K = G.shape
+    if tuple(Up.shape) != (M, K):
+        raise ZqfpError(-2, "gate / up shapes differ")
+    Xq, sx, T, r = _quant_outputs(G, U)
+    _check(lib().zqfp_swiglu_quantize_act_fp8(_ptr(G), _ptr(Up), Up.stride(0), M, K, G.stride(0), _ptr(Xq), _ptr(sx), _ptr(U),
+                                              r, _ptr(T), _stream(G)))
     return (Xq, sx) if U is None else (Xq, sx, T)
 
 

@@ -429,6 +429,90 @@ def test_fused_normalisations_on_rows_beyond_the_register_budget_of_256_threads(
             assert np.all(np.abs(_sync_np(out[2]) - T_o) <= 2.0 ** -18 * Tabs + 1e-30)
 
 
+def _check_quantized(out, Y, U):
+    """out = (Xq, sx[, T]) of a fused quantizer call against the oracle's quantizer applied to the oracle's Y."""
+    Xq_o, sx_o = oracle.quantize_act(Y)
+    assert bits_equal_f32(_sync_np(out[1]), sx_o)
+    assert np.array_equal(_sync_np(out[0]), Xq_o)
+    if U is not None:
+        T_o, Tabs = oracle.lorc_left(Y, U)
+        assert np.all(np.abs(_sync_np(out[2]) - T_o) <= 2.0 ** -18 * Tabs + 1e-30)
+
+
+def _producer_case(K, M, rank, seed):
+    import dataclasses
+    cfg = dataclasses.replace(CFG["llama7b_qkv"], K=K, N=64, G=64, rank=rank, seed=seed)
+    X = inputs.make_x(cfg, M)
+    R = inputs.make_x(dataclasses.replace(cfg, seed=seed + 1), M)
+    U = inputs.make_uv(cfg)[0] if rank else None
+    return X, R, U
+
+
+PRODUCER_SHAPES = [(256, 16, 0), (2048, 300, 0), (4096, 77, 8), (8192, 1030, 0), (4096, 1100, 0), (2048, 1027, 0),
+                   (11008, 40, 8), (28672, 3, 0), (32768, 2, 0), (128, 9, 0), (8320, 70, 8)]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K,M,rank", PRODUCER_SHAPES)
+def test_residual_add_fused_in_front_of_both_normalisations(K, M, rank):
+    """h = bf16(X + R) is written out bit-exactly and is what gets normalised and quantized; H may be R itself."""
+    X, R, U = _producer_case(K, M, rank, 100 + M)
+    g, b = _gain_bits(K), _bias_bits(K)
+    gd = bf16_tensor(g.reshape(1, -1)).reshape(-1).contiguous()
+    bd = bf16_tensor(b.reshape(1, -1)).reshape(-1).contiguous()
+    Ud = f16_tensor(U) if rank else None
+    H_o = oracle.add_bf16(X, R)
+    for bias_dev, Yn in ((None, oracle.rmsnorm_bf16(H_o, g, 1e-5)), (bd, oracle.layernorm_bf16(H_o, g, b, 1e-5))):
+        out = zqfp.add_norm_quantize_act_fp8(bf16_tensor(X), bf16_tensor(R), gd, 1e-5, bias=bias_dev, U=Ud)
+        assert np.array_equal(_sync_np(out[0].view(torch.int16)).view(np.uint16), H_o)
+        _check_quantized(out[1:], Yn, U)
+    # in place: the residual stream is overwritten by the sum; rows of X taken from a wider tensor
+    wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = bf16_tensor(X)
+    Rd = bf16_tensor(R)
+    out = zqfp.add_norm_quantize_act_fp8(wide[:, :K], Rd, gd, 1e-5, U=Ud, H=Rd)
+    assert out[0].data_ptr() == Rd.data_ptr()
+    assert np.array_equal(_sync_np(Rd.view(torch.int16)).view(np.uint16), H_o)
+    _check_quantized(out[1:], oracle.rmsnorm_bf16(H_o, g, 1e-5), U)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K,M,rank", PRODUCER_SHAPES)
+def test_relu_fused_in_front_of_the_quantizer(K, M, rank):
+    X, _, U = _producer_case(K, M, rank, 200 + M)
+    X[M // 2] = inputs.f32_to_bf16_bits(-np.abs(inputs.bf16_bits_to_f32(X[M // 2])))  # a token that ReLU voids entirely
+    out = zqfp.relu_quantize_act_fp8(bf16_tensor(X), f16_tensor(U) if rank else None)
+    _check_quantized(out, oracle.relu_bf16(X), U)
+    assert np.all(_sync_np(out[0])[M // 2] == 0) and _sync_np(out[1])[M // 2] == 1.0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K,M,rank", PRODUCER_SHAPES)
+def test_gated_silu_fused_in_front_of_the_quantizer(K, M, rank):
+    """silu(gate) * up with gate and up taken as the two halves of one [M, 2K] tensor, as a fused gate/up
+    projection would leave them."""
+    G, Up, U = _producer_case(K, M, rank, 300 + M)
+    G = inputs.f32_to_bf16_bits(inputs.bf16_bits_to_f32(G) * np.float32(0.5))
+    both = torch.cat([bf16_tensor(G), bf16_tensor(Up)], dim=1)
+    out = zqfp.swiglu_quantize_act_fp8(both[:, :K], both[:, K:], f16_tensor(U) if rank else None)
+    _check_quantized(out, oracle.swiglu_bf16(G, Up), U)
+
+
+@pytest.mark.gpu
+def test_fused_producer_argument_checks():
+    X = bf16_tensor(inputs.make_x(CFG["tiny"], 4))
+    g = bf16_tensor(_gain_bits(256).reshape(1, -1)).reshape(-1).contiguous()
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.add_norm_quantize_act_fp8(X, X[:2].contiguous(), g, 1e-5)
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.add_norm_quantize_act_fp8(X, X, g, 0.0)
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.swiglu_quantize_act_fp8(X, X[:, :128])
+    lib = zqfp.lib()
+    assert lib.zqfp_swiglu_quantize_act_fp8(X.data_ptr(), None, 256, 4, 256, 256, None, None, None, 0, None, None) != 0
+    assert lib.zqfp_relu_quantize_act_fp8(X.data_ptr(), 4, 65536, 65536, X.data_ptr(), X.data_ptr(), None, 0, None, None) != 0
+
+
 @pytest.mark.gpu
 def test_fused_layernorm_quantizer_argument_checks():
     X = bf16_tensor(inputs.make_x(CFG["tiny"], 4))
