@@ -68,7 +68,7 @@ def timed_replays(g, replays, settle_s=0.06):
 
 
 class Workload:
-    def __init__(self, name, M, accum, copies=1):
+    def __init__(self, name, M, accum, copies=1, out_dtype=torch.float32):
         self.cfg = cfg = inputs.CONFIGS[name]
         self.name, self.M, self.accum = name, M, accum
         self.X = bf16_dev(inputs.make_x(cfg, M))
@@ -80,9 +80,9 @@ class Workload:
         if cfg.rank:
             U, V = inputs.make_uv(cfg)
             self.U, self.V = f16_dev(U), f16_dev(V)
-        self.Y = torch.empty((M, cfg.N), dtype=torch.float32, device="cuda")
+        self.Y = torch.empty((M, cfg.N), dtype=out_dtype, device="cuda")
         self.flops = 2.0 * M * cfg.K * cfg.N
-        self.bytes = algorithmic_bytes(cfg, M)
+        self.bytes = algorithmic_bytes(cfg, M, self.Y.element_size())
         self.i = 0
 
     def step(self, ev=None):
@@ -162,6 +162,7 @@ class Workload:
         gbs = self.bytes / (gemm_ms * 1e-3) / 1e9
         return {
             "workload": f"{self.name} M={self.M}", "accum": "exact" if self.accum == 0 else "fast",
+            "out": "f32" if self.Y.dtype == torch.float32 else "bf16",
             "ms_per_step": round(ms, 5), "gemm_ms": round(gemm_ms, 5),
             "step_tflops": round(self.flops / (ms * 1e-3) / 1e12, 3),
             "gemm_tflops": round(tflops, 3), "gemm_gbs": round(gbs, 1),
@@ -354,14 +355,15 @@ def main():
         also = []
         plan = [
             ("llama7b_qkv", 4096, zqfp.ACCUM_FAST, 1),
+            ("llama7b_qkv", 4096, accum, 1, torch.bfloat16),
             ("llama7b_ffn_up", 4096, accum, 1),
             ("llama13b_ffn_lorc", 2048, accum, 1),
             ("llama7b_qkv", 16, accum, 24),
             ("llama70b_ffn_decode", 16, accum, 5),
             ("llama70b_ffn_decode", 1, accum, 5),
         ]
-        for name, M, acc, copies in plan:
-            wl = Workload(name, M, acc, copies)
+        for name, M, acc, copies, *odt in plan:
+            wl = Workload(name, M, acc, copies, *odt)
             also.append(wl.summary(max(10, args.steps), args.warmup))
             del wl
             torch.cuda.empty_cache()
