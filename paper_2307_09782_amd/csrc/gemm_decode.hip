@@ -186,10 +186,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     // The loop is unrolled by NB so that the fragment buffers are addressed statically.  The LDS
     // reduction buffer alternates per strip: it is rewritten two strips later, after a barrier
     // that every reader has passed.
-    const int64_t stride = gridDim.x / nchunks;  // workgroups per chunk
-    int64_t s = blockIdx.x / nchunks;
+    // Strip order.  Consecutive workgroup ids sit on consecutive XCDs (8 of them, one L2 each).  A
+    // strip's 16 output columns are half a 128-byte line of every row of Y, so the two strips of a
+    // line go to the same XCD, to neighbouring workgroups in the same step: its L2 then merges the
+    // halves and writes whole lines.  Workgroup (xcd, loc) walks q = loc, loc + grid/8, ... of its
+    // XCD's list, whose entry q is strip 2 * (8 * (q / 2) + xcd) + q % 2 (increasing in q).
+    const bool paired = nchunks == 1 && (gridDim.x & 7) == 0;
+    const int64_t stride = paired ? gridDim.x >> 3 : gridDim.x / nchunks;
+    int64_t q = paired ? blockIdx.x >> 3 : blockIdx.x / nchunks;
+    const int xcd = blockIdx.x & 7;
+    auto strip_of = [&](int64_t qq) { return paired ? 2 * (8 * (qq >> 1) + xcd) + (qq & 1) : qq; };
 #pragma unroll
-    for (int r = 0; r < NB - 1; ++r) issue(r, s + r * stride);
+    for (int r = 0; r < NB - 1; ++r) issue(r, strip_of(q + r * stride));
 #pragma unroll
     for (int u = 0; u < KPW; ++u) {
         const bool live = wave + kWaves * u < nkt;  // uniform
@@ -212,13 +220,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     while (true) {
 #pragma unroll
         for (int r = 0; r < NB; ++r) {
-            issue((r + NB - 1) % NB, s + (NB - 1) * stride);
+            issue((r + NB - 1) % NB, strip_of(q + (NB - 1) * stride));
             __builtin_amdgcn_sched_barrier(0);
-            finish(r, s, par);
+            finish(r, strip_of(q), par);
             __builtin_amdgcn_sched_barrier(0);
             par ^= 1;
-            s += stride;
-            if (s >= nstrips) return;
+            q += stride;
+            if (strip_of(q) >= nstrips) return;
         }
     }
 }

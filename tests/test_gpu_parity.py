@@ -207,6 +207,11 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (16, 11008, 96, 128, 1, 8),     # M <= 16 beyond 64 k-tiles, few strips: streaming fallback with LoRC
     (3, 8320, 80, 64, 2, 0),        # the same with 65 k-tiles, groups of 64
     (9, 28672, 48, 128, 1, 0),      # the same with 224 k-tiles
+    # decode form with a workgroup count that is a multiple of 8 (strips handed out in pairs per XCD):
+    (16, 256, 128, 128, 1, 0),      # 8 strips on 8 workgroups: half of them start past the last strip
+    (5, 512, 1664, 128, 2, 8),      # 104 strips on 104 workgroups, some start past the end
+    (16, 256, 4100, 128, 1, 0),     # 257 strips on 256 workgroups: one ragged strip in the second round
+    (2, 384, 6000, 128, 1, 3),      # 375 strips on 256 workgroups
 ])
 def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
