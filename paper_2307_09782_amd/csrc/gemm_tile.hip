@@ -110,11 +110,13 @@ struct TileCfg {
     static constexpr int E_BYTES = THREADS * 4;               // one exponent dword per output channel (first BN used)
     static constexpr int STAGE = A_BYTES + B_BYTES + E_BYTES;
     static constexpr int NSTAGE = NSTAGE_;
-    static_assert(NSTAGE == 2 || NSTAGE == 3, "the loop keeps one or two k-tiles in flight behind the one it multiplies");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the loop keeps NSTAGE - 1 k-tiles in flight behind the one it multiplies");
     static constexpr int A_CHUNKS = A_BYTES / 16 / THREADS;  // 16 B chunks per thread
     static constexpr int B_CHUNKS = B_BYTES / 16 / THREADS;
     static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile / thread mismatch");
     static_assert(BN <= THREADS, "one exponent dword per thread");
+    static_assert((NSTAGE - 1) * (A_CHUNKS + B_CHUNKS + 1) <= 63, "outstanding loads must fit the 6-bit load counter");
+    static_assert(NSTAGE * STAGE <= 160 * 1024, "stages exceed the LDS of a compute unit");
 };
 
 // Two waves per SIMD in every configuration (8-wave workgroups alone on a compute unit, 4-wave
@@ -351,25 +353,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         wait_loads_then_barrier<decltype(wait_tag)::value>();
     };
 
-    // ---- prologue: k-tiles 0 .. NSTAGE - 1 into stages of the same number; the first operands into registers
+    // ---- prologue: k-tiles 0 .. NSTAGE - 1 (as far as they exist) into stages of the same number; the
+    // first operands into registers.  The fetch cursor ends at k-tile NSTAGE when more will be requested.
+    static_for<0, NSTAGE>([&](auto t_tag) __attribute__((always_inline)) {
+        constexpr int TILE = decltype(t_tag)::value;
+        if (TILE < nkt) {
+            if constexpr (TILE > 0) advance(cur_load);
 #pragma unroll
-    for (int t = 0; t < NSIDE; ++t) side_load(t, 0, 0, cur_load);
-    if (nkt > 1) {
-        advance(cur_load);
-#pragma unroll
-        for (int t = 0; t < NSIDE; ++t) side_load(t, 1, 1, cur_load);
-        if constexpr (NSTAGE == 2) advance(cur_load);  // now at k-tile 2
-    }
-    if constexpr (NSTAGE == 3) {
-        if (nkt > 2) {
-            advance(cur_load);
-#pragma unroll
-            for (int t = 0; t < NSIDE; ++t) side_load(t, 2, 2, cur_load);
-            advance(cur_load);  // now at k-tile 3
+            for (int t = 0; t < NSIDE; ++t) side_load(t, TILE, TILE, cur_load);
         }
-    }
-    // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done
-    if (NSTAGE == 3 && nkt > 2) wait_loads_then_barrier<2 * NSIDE>();
+    });
+    if (nkt >= NSTAGE) advance(cur_load);
+    // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done (waiting for
+    // more than necessary is always safe: loads complete in order)
+    if (nkt >= NSTAGE) wait_loads_then_barrier<(NSTAGE - 1) * NSIDE>();
     else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
     else wait_loads_then_barrier<0>();
     ta = lds_read16<0>(a_addr0);
@@ -386,18 +383,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         for (int d = 0; d < 8; ++d) split_in_place(fy, d);
     }
 
-    // ---- main loop.  Step kt computes stage kt % NSTAGE; the k-tiles behind it (kt + 1, and kt + 2 with
-    // three stages) are in the other stages or on their way, k-tile kt + NSTAGE is requested into
-    // stage kt % NSTAGE behind the step's barrier: two steps of slack for the memory latency with three
-    // stages, most of one with two (two workgroups then share a compute unit and fill each other's
-    // gaps).  The loop is rotated so that no LDS read is in flight across its back edge: an iteration is
+    // ---- main loop.  Step kt computes stage kt % NSTAGE; the k-tiles behind it (kt + 1 .. kt + NSTAGE - 1)
+    // are in the other stages or on their way, k-tile kt + NSTAGE is requested into
+    // stage kt % NSTAGE behind the step's barrier: NSTAGE - 1 steps of slack for the memory latency
+    // (most of one with two stages, where two workgroups share a compute unit and fill each other's
+    // gaps; five with the six stages of the small tile, whose lone workgroup is a weight stream).  The loop is rotated so that no LDS read is in flight across its back edge: an iteration is
     // the last row block of step kt followed by the first blocks of step kt + 1 and that step's barrier,
-    // at which the loads of k-tile kt + 2 must have landed and only younger ones (three stages: those of
-    // k-tile kt + 3) may be outstanding.  The last steps request nothing and are peeled.
+    // at which the loads of k-tile kt + 2 must have landed and only younger ones (those of k-tiles
+    // kt + 3 .. kt + NSTAGE) may be outstanding.  The last steps request nothing and are peeled.
     using W1 = std::integral_constant<int, (NSTAGE - 2) * NSIDE>;
     using W0 = std::integral_constant<int, 0>;
     int stage = 0;
-    if (nkt > 2) head_blocks(0, 0, W1{});
+    if (nkt >= NSTAGE) head_blocks(0, 0, W1{});  // k-tiles 2 .. NSTAGE - 1 may still be on their way
     else head_blocks(0, 0, W0{});
     int kt = 0;
     for (; kt + NSTAGE < nkt; ++kt) {  // k-tile kt + NSTAGE exists
