@@ -361,6 +361,9 @@ def main():
             ("llama7b_qkv", 16, accum, 24),
             ("llama70b_ffn_decode", 16, accum, 5),
             ("llama70b_ffn_decode", 1, accum, 5),
+            ("llama7b_ffn_down", 4096, accum, 1),
+            ("llama7b_attn_out", 4096, accum, 1),
+            ("llama70b_ffn_down", 16, accum, 5),
         ]
         for name, M, acc, copies, *odt in plan:
             wl = Workload(name, M, acc, copies, *odt)

@@ -54,6 +54,11 @@ CONFIGS = {
     "llama7b_ffn_up": Config("llama7b_ffn_up", 4096, 11008, (1, 16, 256, 4096), 128, 1, 0.01, 0, 20.0),
     "llama13b_ffn_lorc": Config("llama13b_ffn_lorc", 5120, 13824, (16, 2048), 128, 1, 0.01, 0, 20.0, rank=8),
     "llama70b_ffn_decode": Config("llama70b_ffn_decode", 8192, 28672, (1, 4, 16, 64), 128, 1, 0.01, 0, 50.0, rank=8),
+    # long K into few output channels: the down projections and the attention output of the same models
+    "llama7b_ffn_down": Config("llama7b_ffn_down", 11008, 4096, (16, 4096), 128, 1, 0.01, 0, 20.0),
+    "llama13b_ffn_down": Config("llama13b_ffn_down", 13824, 5120, (16, 2048), 128, 1, 0.01, 0, 20.0, rank=8),
+    "llama70b_ffn_down": Config("llama70b_ffn_down", 28672, 8192, (1, 16, 64), 128, 1, 0.01, 0, 50.0, rank=8),
+    "llama7b_attn_out": Config("llama7b_attn_out", 4096, 4096, (16, 4096), 128, 1, 0.01, 0, 20.0),
 }
 
 

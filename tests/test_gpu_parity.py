@@ -241,6 +241,10 @@ FULL = [
     ("llama7b_ffn_up", 1), ("llama7b_ffn_up", 16), ("llama7b_ffn_up", 256), ("llama7b_ffn_up", 4096),
     ("llama13b_ffn_lorc", 16), ("llama13b_ffn_lorc", 2048),
     ("llama70b_ffn_decode", 1), ("llama70b_ffn_decode", 4), ("llama70b_ffn_decode", 16), ("llama70b_ffn_decode", 64),
+    # long K, few output channels (down projections, attention output): chunked decode form, K-split tiles
+    ("llama7b_ffn_down", 16), ("llama7b_ffn_down", 4096), ("llama13b_ffn_down", 16), ("llama13b_ffn_down", 2048),
+    ("llama70b_ffn_down", 1), ("llama70b_ffn_down", 16), ("llama70b_ffn_down", 64),
+    ("llama7b_attn_out", 16), ("llama7b_attn_out", 4096),
 ]
 
 
