@@ -253,3 +253,31 @@ def lorc_left(X, U):
 
 def max_threads():
     return lib().orc_max_threads()
+
+
+# ---- LoRC factorisation (offline step; plain numpy in float64) -------------------
+def _bf16_bits_to_f64(bits):
+    return (np.asarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def dequant_weight(codes, exps, c, G):
+    """The quantized weight the GEMM multiplies with, W^[k,n] = c[n] * 2^(exps[k/G,n] - 127) * e2m1(codes[k,n])
+    (Section 3, "Casting the FP4 to FP8": S = 2^n, methods M1 / M2), as float64 [K,N]."""
+    _chk(codes, np.uint8, 2), _chk(exps, np.uint8, 2), _chk(c, np.float32, 1)
+    K, N = codes.shape
+    table = np.array([e2m1_decode(q) for q in range(16)], np.float64)
+    scale = np.exp2(exps.astype(np.float64) - 127.0)           # [K/G, N]
+    return table[codes] * np.repeat(scale, G, axis=0) * c.astype(np.float64)[None, :]
+
+
+def lorc_factors(W, codes, exps, c, G, r):
+    """LoRC (Section 3): singular value decomposition of the error matrix E = W - W^ (original minus
+    quantized weight), E = P diag(s) Q^T; the two low-rank matrices are the r leading singular triplets
+    with the singular values shared evenly, U = P_r diag(s_r)^(1/2), V = diag(s_r)^(1/2) Q_r^T, so that U V is the
+    best rank-r approximation of E.  W: bf16 bits [K,N].  Returns U [K,r], V [r,N], s [min(K,N)] (float64)
+    and E."""
+    _chk(W, np.uint16, 2)
+    E = _bf16_bits_to_f64(W) - dequant_weight(codes, exps, c, G)
+    P, s, Qt = np.linalg.svd(E, full_matrices=False)
+    root = np.sqrt(s[:r])
+    return P[:, :r] * root[None, :], root[:, None] * Qt[:r], s, E
