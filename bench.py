@@ -231,6 +231,27 @@ def quantizer_rows(name="llama7b_qkv", M=4096):
     return rows
 
 
+def offline_rows(name="llama7b_qkv", r=8, power_iters=2):
+    """The LoRC factorisation of one layer's quantization error (offline step): time, and the rate at which
+    it streams the float32 error matrix (one write, 2 + 2 * power_iters reads, plus W and the packed weight)."""
+    cfg = inputs.CONFIGS[name]
+    W = bf16_dev(inputs.make_w(cfg))
+    packed = zqfp.pack_weight_fp4(W, cfg.G, cfg.mode)
+    omega = torch.randn((cfg.N, r + 8), dtype=torch.float32, device="cuda")
+    zqfp.lorc_factorize(W, packed, cfg.G, r, omega, power_iters)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(3):
+        zqfp.lorc_factorize(W, packed, cfg.G, r, omega, power_iters)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / 3
+    nbytes = cfg.K * cfg.N * (2 + 0.5 + 4 + 4 * (2 + 2 * power_iters))
+    return [{"call": "lorc_factorize", "workload": f"{name} K={cfg.K} N={cfg.N} rank {r}, {power_iters} power iterations",
+             "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1)}]
+
+
 def measured_ceilings():
     """What the device itself sustains right now (measurement probes of the library, timed with HIP
     events): a plain streaming read of 2 GiB, twice the last-level cache eight times over, and a
@@ -374,6 +395,7 @@ def main():
 
     if not args.no_also:
         out["quantizer"] = quantizer_rows()
+        out["offline"] = offline_rows()
         ceil = measured_ceilings()
         rf = out["roofline"]
         ceil["frac_of_measured"] = round(rf["achieved"] / (ceil["stream_read_gbs"] if rf["bound"] == "hbm" else ceil["mfma_fp8xfp4_tflops"]), 4)

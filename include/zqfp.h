@@ -226,6 +226,37 @@ int zqfp_pack_weight_fp4(const void *W, int64_t K, int64_t N, int64_t ldw,
                          int G, int mode, void *packed, void *stream);
 
 /*
+ * lorc_factorize -- the two low-rank matrices of LoRC (paper Section 3: singular
+ * value decomposition of the error matrix E = W - W^, the original weight minus
+ * the quantized one; Appendix A: rank 8 for LLaMA, 16..56 for OPT).  Offline
+ * step.  U V is the rank-r approximation of E from its r leading singular
+ * triplets, with the singular values shared evenly between the factors,
+ *   U = P_r diag(s_r)^(1/2),  V = diag(s_r)^(1/2) Q_r^T   (E = P diag(s) Q^T),
+ * found by a subspace iteration with r + 8 columns and `power_iters` rounds
+ * (2 is enough for quantization error, whose spectrum is flat), so that the
+ * residual |E - U V|_F is within a fraction of a percent of the optimum.
+ *
+ *   W        [K, N] bfloat16, row stride ldw                           (in)
+ *   packed   the blob zqfp_pack_weight_fp4 made (of W, or of any K x N
+ *            matrix: E is W minus whatever the blob de-quantizes to)     (in)
+ *   r        rank, 1..64, with r + 8 <= min(K, N)
+ *   Omega    [N, r + 8] float32 (16-byte aligned), independent standard
+ *            normal draws; the caller supplies them so that the result is
+ *            reproducible                                                (in)
+ *   U        [K, r] binary16      V  [r, N] binary16                     (out)
+ *   sigma    [r] float32: the r leading singular values of E, descending (out)
+ *   workspace  zqfp_lorc_workspace_bytes(K, N, r) bytes of device memory,
+ *            256-byte aligned (E in float32 and the iteration's blocks)
+ * Returns ZQFP_E_SHAPE for a rank or iteration count outside the limits.
+ */
+size_t zqfp_lorc_workspace_bytes(int64_t K, int64_t N, int r);
+int zqfp_lorc_factorize(const void *W, int64_t K, int64_t N, int64_t ldw,
+                        const void *packed, int G, int r,
+                        const float *Omega, int power_iters,
+                        void *U, void *V, float *sigma,
+                        void *workspace, void *stream);
+
+/*
  * unpack_codes -- canonical view of a packed blob, for bit-exact comparison
  * and inspection (same K, N, G as at packing time).
  *   codes    [K, N] uint8, one E2M1 code (0..15, bit 3 = sign) per byte  (out)

@@ -48,7 +48,7 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
 
 extern "C" {
 
-int zqfp_version(void) { return 103; }
+int zqfp_version(void) { return 104; }
 
 const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
 
@@ -181,6 +181,28 @@ int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K
                         void* workspace, void* stream)
 {
     return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, stream);
+}
+
+size_t zqfp_lorc_workspace_bytes(int64_t K, int64_t N, int r)
+{
+    if (K <= 0 || N <= 0 || r < 1 || r > 64) return 0;
+    return zqfp::lorc_workspace_bytes(K, N, r);
+}
+
+int zqfp_lorc_factorize(const void* W, int64_t K, int64_t N, int64_t ldw, const void* packed, int G, int r,
+                        const float* Omega, int power_iters, void* U, void* V, float* sigma, void* workspace, void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L) || N == 0 || ldw < N) return ZQFP_E_SHAPE;
+    if (r < 1 || r > 64 || r + 8 > K || r + 8 > N || power_iters < 0 || power_iters > 8) return ZQFP_E_SHAPE;
+    if (!W || !packed || !Omega || !U || !V || !sigma || !workspace) return ZQFP_E_NULL;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0 || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+        !aligned16(Omega))
+        return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_lorc_factorize(static_cast<const uint16_t*>(W), ldw, static_cast<const uint8_t*>(packed), L, r,
+                                               Omega, power_iters, static_cast<uint16_t*>(U), static_cast<uint16_t*>(V),
+                                               sigma, workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
 int zqfp_probe_stream_read(const void* src, int64_t bytes, void* sink, int workgroups, void* stream)

@@ -191,6 +191,11 @@ bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace
 // Y[m,n] = (sx[m] c[n]) * sum_s partial[s][m][n] (+ T.V): the second kernel of every K-split
 hipError_t launch_splitk_reduce(const float* partial, int slices, int64_t M, const uint8_t* blob, const BlobLayout& L,
                                 const float* sx, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s);
+// LoRC factorisation of W - W^ (offline): U [K, r], V [r, N] binary16, sigma [r]; Omega [N, r + 8] float32
+size_t lorc_workspace_bytes(int64_t K, int64_t N, int r);
+hipError_t launch_lorc_factorize(const uint16_t* W, int64_t ldw, const uint8_t* blob, const BlobLayout& L, int r,
+                                 const float* Omega, int power_iters, uint16_t* U, uint16_t* V, float* sigma,
+                                 void* workspace, hipStream_t s);
 hipError_t launch_probe_read(const void* src, int64_t bytes, uint32_t* sink, int workgroups, hipStream_t s);
 hipError_t launch_probe_mfma(const uint32_t* operands, float* sink, int iters, int workgroups, hipStream_t s);
 

@@ -67,6 +67,10 @@ def lib():
         L.zqfp_relu_quantize_act_fp8.argtypes = [p, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_swiglu_quantize_act_fp8.restype = c.c_int
         L.zqfp_swiglu_quantize_act_fp8.argtypes = [p, p, i64, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_lorc_workspace_bytes.restype = c.c_size_t
+        L.zqfp_lorc_workspace_bytes.argtypes = [i64, i64, c.c_int]
+        L.zqfp_lorc_factorize.restype = c.c_int
+        L.zqfp_lorc_factorize.argtypes = [p, i64, i64, i64, p, c.c_int, c.c_int, p, c.c_int, p, p, p, p, p]
         L.zqfp_probe_stream_read.restype = c.c_int
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
         L.zqfp_probe_mfma.restype = c.c_int
@@ -270,6 +274,23 @@ def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=AC
     _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
                                      Y.stride(0), code, accum, _ptr(ws), _stream(Xq)))
     return Y
+
+
+def lorc_factorize(W, packed, G, r, Omega, power_iters=2):
+    """LoRC factors of W minus what `packed` de-quantizes to: U [K,r] fp16, V [r,N] fp16, sigma [r] f32.
+    Omega [N, r+8] float32 holds the caller's standard normal draws."""
+    _rows(W, torch.bfloat16), _dev(packed, torch.uint8, 1), _dev(Omega, torch.float32, 2)
+    K, N = W.shape
+    if tuple(Omega.shape) != (N, r + 8):
+        raise ZqfpError(-2, "Omega must be [N, r + 8]")
+    U = torch.empty((K, r), dtype=torch.float16, device=W.device)
+    V = torch.empty((r, N), dtype=torch.float16, device=W.device)
+    sigma = torch.empty((r,), dtype=torch.float32, device=W.device)
+    ws = torch.empty((int(lib().zqfp_lorc_workspace_bytes(K, N, r)) + 256,), dtype=torch.uint8, device=W.device)
+    off = (-ws.data_ptr()) % 256
+    _check(lib().zqfp_lorc_factorize(_ptr(W), K, N, W.stride(0), _ptr(packed), G, r, _ptr(Omega), power_iters, _ptr(U),
+                                     _ptr(V), _ptr(sigma), ws.data_ptr() + off, _stream(W)))
+    return U, V, sigma
 
 
 def probe_stream_read(src, sink, workgroups):

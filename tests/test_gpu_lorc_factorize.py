@@ -1,0 +1,99 @@
+"""LoRC factorisation on the GPU against the oracle's singular value decomposition (Section 3).  The factors
+themselves are not unique (signs, and any rotation inside a cluster of equal singular values), so the tests
+compare what is: the singular values, the residual |E - U V|_F against the Eckart-Young optimum, the product
+U V where the spectrum has a gap, and the even split of the singular values between the factors."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2307_09782_amd import inputs, zqfp
+from _util import bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+
+def _omega(N, l, seed):
+    return torch.from_numpy(np.random.default_rng(seed).standard_normal((N, l)).astype(np.float32)).cuda()
+
+
+def _run(W_bits, W0_bits, G, mode, r, power_iters, seed=0):
+    """GPU factors of W - dequant(pack(W0)) and the oracle's for the same pair."""
+    packed = zqfp.pack_weight_fp4(bf16_tensor(W0_bits), G, mode)
+    U, V, sigma = zqfp.lorc_factorize(bf16_tensor(W_bits), packed, G, r, _omega(W_bits.shape[1], r + 8, seed), power_iters)
+    torch.cuda.synchronize()
+    codes, exps, c, _ = oracle.pack_weight(W0_bits, G, mode)
+    Uo, Vo, so, E = oracle.lorc_factors(W_bits, codes, exps, c, G, r)
+    return U.double().cpu().numpy(), V.double().cpu().numpy(), sigma.double().cpu().numpy(), Uo, Vo, so, E
+
+
+@pytest.mark.parametrize("K,N,G,mode,r", [(512, 384, 128, 1, 8), (1024, 200, 256, 2, 5), (256, 1024, 64, 1, 16)])
+def test_error_matrix_with_a_spectral_gap(K, N, G, mode, r):
+    """W = W0 + a rank-r matrix well above the quantization noise, quantized weight from W0 alone: the leading
+    triplets of E are those of the planted matrix and everything unique about them must agree."""
+    cfg = dataclasses.replace(inputs.CONFIGS["tiny"], K=K, N=N, G=G, mode=mode, seed=K + N)
+    W0 = inputs.make_w(cfg)
+    rng = np.random.default_rng(7)
+    P, _ = np.linalg.qr(rng.standard_normal((K, r)))
+    Q, _ = np.linalg.qr(rng.standard_normal((N, r)))
+    s = np.geomspace(4.0, 0.5, r)  # the quantization noise sits near 0.1
+    W = inputs.f32_to_bf16_bits((inputs.bf16_bits_to_f32(W0) + (P * s) @ Q.T).astype(np.float32))
+    U, V, sigma, Uo, Vo, so, E = _run(W, W0, G, mode, r, 2)
+    assert np.all(np.abs(sigma - so[:r]) <= 2e-3 * so[:r]), (sigma, so[:r])
+    res, opt = np.linalg.norm(E - U @ V), np.linalg.norm(E - Uo @ Vo)
+    print(f"residual {res:.6f} optimum {opt:.6f} ratio {res / opt:.6f}; sigma_r {so[r - 1]:.4f} next {so[r]:.4f}")
+    assert res <= 1.002 * opt
+    assert np.linalg.norm(U @ V - Uo @ Vo) <= 2e-2 * np.linalg.norm(Uo @ Vo)
+    # singular values shared evenly: U^T U = V V^T = diag(sigma), to binary16 accuracy
+    assert np.allclose(U.T @ U, np.diag(so[:r]), atol=5e-3 * so[0])
+    assert np.allclose(V @ V.T, np.diag(so[:r]), atol=5e-3 * so[0])
+
+
+@pytest.mark.parametrize("name,K,N,G,mode,r", [("tiny", 256, 256, 128, 1, 8), ("opt1p3b_fc1", 2048, 512, 256, 2, 16),
+                                              ("tiny", 384, 200, 128, 1, 3), ("llama7b_qkv", 1024, 1536, 128, 1, 8)])
+def test_plain_quantization_error_is_compensated_close_to_the_optimum(name, K, N, G, mode, r):
+    """E = W - W^ of the synthetic weights: a flat spectrum, where the factors are far from unique; the residual
+    and the captured energy are what can be compared."""
+    cfg = dataclasses.replace(inputs.CONFIGS[name], K=K, N=N, G=G, mode=mode)
+    W = inputs.make_w(cfg)
+    U, V, sigma, Uo, Vo, so, E = _run(W, W, G, mode, r, 4)
+    res, opt, e0 = np.linalg.norm(E - U @ V), np.linalg.norm(E - Uo @ Vo), np.linalg.norm(E)
+    cap, cap_o = np.sum(sigma ** 2), np.sum(so[:r] ** 2)
+    print(f"|E| {e0:.5f} residual {res:.5f} optimum {opt:.5f} ratio {res / opt:.5f}; captured {cap / cap_o:.4f} of the optimum")
+    assert res < e0                      # the compensation reduces the weight error ...
+    assert res <= 1.01 * opt             # ... to within a percent of the best any rank-r pair can do
+    assert np.all(sigma <= so[:r] * (1 + 1e-3)) and cap >= 0.85 * cap_o
+    assert np.all(np.diff(sigma) <= 0)   # descending
+
+
+def test_factors_plug_into_the_gemm_and_reduce_its_error():
+    """End to end on the tiny configuration: Y with the device-made factors is closer to X W than Y without."""
+    cfg = inputs.CONFIGS["tiny"]
+    W, X = inputs.make_w(cfg), inputs.make_x(cfg, 16)
+    Wd, Xd = bf16_tensor(W), bf16_tensor(X)
+    packed = zqfp.pack_weight_fp4(Wd, cfg.G, cfg.mode)
+    U, V, _ = zqfp.lorc_factorize(Wd, packed, cfg.G, 8, _omega(cfg.N, 16, 1), 2)
+    Xq, sx, T = zqfp.quantize_act_fp8(Xd, U)
+    Y1 = zqfp.w4a8_gemm_lorc(Xq, sx, packed, cfg.N, cfg.G, T, V).double().cpu().numpy()
+    Y0 = zqfp.w4a8_gemm(Xq, sx, packed, cfg.N, cfg.G).double().cpu().numpy()
+    # reference with the same quantized activations, so that only the weight error is compared
+    Xq_o, sx_o = oracle.quantize_act(X)
+    table = np.array([oracle.e4m3_decode(q) for q in range(256)])
+    Xdq = table[Xq_o] * sx_o[:, None].astype(np.float64)
+    ref = Xdq @ inputs.bf16_bits_to_f32(W).astype(np.float64)
+    assert np.linalg.norm(Y1 - ref) < np.linalg.norm(Y0 - ref)
+
+
+def test_argument_checks():
+    cfg = inputs.CONFIGS["tiny"]
+    Wd = bf16_tensor(inputs.make_w(cfg))
+    packed = zqfp.pack_weight_fp4(Wd, cfg.G, cfg.mode)
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.lorc_factorize(Wd, packed, cfg.G, 8, _omega(cfg.N, 15, 0))
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.lorc_factorize(Wd, packed, cfg.G, 65, _omega(cfg.N, 73, 0))
+    with pytest.raises(zqfp.ZqfpError):
+        zqfp.lorc_factorize(Wd, packed, cfg.G, 8, _omega(cfg.N, 16, 0), power_iters=9)
+    assert zqfp.lib().zqfp_lorc_workspace_bytes(256, 256, 0) == 0
