@@ -379,8 +379,14 @@ def main():
             ("llama7b_qkv", 4096, accum, 1, torch.bfloat16),
             ("llama7b_ffn_up", 4096, accum, 1),
             ("llama13b_ffn_lorc", 2048, accum, 1),
+            ("opt1p3b_fc1", 2048, accum, 1),
+            ("llama7b_qkv", 256, accum, 1),
             ("llama7b_qkv", 16, accum, 24),
+            ("llama7b_qkv", 1, accum, 24),
+            ("llama13b_ffn_lorc", 16, accum, 9),
+            ("llama70b_ffn_decode", 64, accum, 5),
             ("llama70b_ffn_decode", 16, accum, 5),
+            ("llama70b_ffn_decode", 4, accum, 5),
             ("llama70b_ffn_decode", 1, accum, 5),
             ("llama7b_ffn_down", 4096, accum, 1),
             ("llama7b_attn_out", 4096, accum, 1),

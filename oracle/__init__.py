@@ -281,3 +281,72 @@ def lorc_factors(W, codes, exps, c, G, r):
     P, s, Qt = np.linalg.svd(E, full_matrices=False)
     root = np.sqrt(s[:r])
     return P[:, :r] * root[None, :], root[:, None] * Qt[:r], s, E
+
+
+# ---- GPTQ with the E2M1 grid and power-of-two scales (offline step; plain numpy in float64) -------
+_E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def e2m1_encode_array(y):
+    """Nearest E2M1 code of every element (ties to the even code, saturating at 6, sign bit copied from y):
+    the array form of orc_e2m1_encode, written out as the definition."""
+    y = np.asarray(y, np.float64)
+    a = np.abs(y)
+    d = np.abs(a[..., None] - _E2M1_GRID)                 # distance to the eight magnitudes
+    best = d.min(axis=-1)
+    cand = d == best[..., None]                           # one or (on a tie) two neighbouring codes
+    lo = cand.argmax(axis=-1)
+    hi = 7 - cand[..., ::-1].argmax(axis=-1)
+    mag = np.where(lo % 2 == 0, lo, hi)                   # the even one of the two
+    return (mag | (np.signbit(y).astype(np.int64) << 3)).astype(np.uint8)
+
+
+def gptq_fp4(W, Hinv_u, G, mode):
+    """GPTQ (the weight quantizer the paper runs, Section 3 and Appendix A) on the E2M1 grid with the
+    power-of-two scales of "Casting the FP4 to FP8" (mode 1 = M1, 2 = M2).
+
+    W: bf16 bits [K, N] (input channels x output channels).  Hinv_u: the upper Cholesky factor of the inverse
+    Hessian, inv(H) = Hinv_u^T Hinv_u, float64 [K, K].  Input channels are quantized one at a time, in order;
+    after channel k its scaled error is pushed onto the channels not yet quantized:
+        q_k = S * e2m1(w_k / S);   err = (w_k - q_k) / Hinv_u[k, k];   w_j -= Hinv_u[k, j] * err  for j > k.
+    A group's scale is fixed when its first channel is reached, from the weights as they stand then
+    (M1: S = 2^n, least n with amax <= 6 * 2^n; M2: S = c * 2^-k with c = column absmax of the ORIGINAL W / 6,
+    least k >= 0 with amax_max <= amax * 2^k, at most 15).
+    Returns codes [K,N] u8, exps [K/G,N] u8, c [N] f32 and the final de-quantized weight [K,N] f64."""
+    _chk(W, np.uint16, 2)
+    K, N = W.shape
+    Wf = _bf16_bits_to_f64(W).copy()
+    codes = np.zeros((K, N), np.uint8)
+    exps = np.zeros((K // G, N), np.uint8)
+    Q = np.zeros((K, N))
+    c = np.ones(N, np.float32)
+    colmax = np.abs(Wf).max(axis=0)
+    if mode == 2:
+        c = np.where(colmax > 0, (colmax.astype(np.float32) / np.float32(6.0)), np.float32(1.0)).astype(np.float32)
+    S = np.ones(N)
+    for k in range(K):
+        if k % G == 0:
+            amax = np.abs(Wf[k:k + G]).max(axis=0)
+            if mode == 1:
+                n = np.zeros(N, np.int64)
+                nz = amax > 0
+                n[nz] = np.ceil(np.log2(amax[nz] / 6.0)).astype(np.int64)
+                # the logarithm can be off by one at exact powers of two: settle it by the definition
+                n[nz & (amax > 6.0 * np.exp2(n))] += 1
+                n[nz & (amax <= 6.0 * np.exp2(n - 1.0))] -= 1
+                n = np.clip(n, -126, 127)
+                exps[k // G] = (n + 127).astype(np.uint8)
+                S = np.exp2(n.astype(np.float64))
+            else:
+                kg = np.full(N, 15, np.int64)
+                nz = amax > 0
+                for t in range(14, -1, -1):
+                    kg[nz & (colmax <= amax * 2.0 ** t)] = t
+                exps[k // G] = (127 - kg).astype(np.uint8)
+                S = c.astype(np.float64) * np.exp2(-kg.astype(np.float64))
+        codes[k] = e2m1_encode_array(Wf[k] / S)
+        Q[k] = np.where(codes[k] & 8, -1.0, 1.0) * _E2M1_GRID[codes[k] & 7] * S
+        err = (Wf[k] - Q[k]) / Hinv_u[k, k]
+        if k + 1 < K:
+            Wf[k + 1:] -= np.outer(Hinv_u[k, k + 1:], err)
+    return codes, exps, c, Q
