@@ -248,8 +248,20 @@ def offline_rows(name="llama7b_qkv", r=8, power_iters=2):
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / 3
     nbytes = cfg.K * cfg.N * (2 + 0.5 + 4 + 4 * (2 + 2 * power_iters))
-    return [{"call": "lorc_factorize", "workload": f"{name} K={cfg.K} N={cfg.N} rank {r}, {power_iters} power iterations",
+    rows = [{"call": "lorc_factorize", "workload": f"{name} K={cfg.K} N={cfg.N} rank {r}, {power_iters} power iterations",
              "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1)}]
+    # GPTQ on the same layer: the float32 matrix products behind the row blocks dominate (K^2 N multiply-adds)
+    U = torch.triu(torch.randn((cfg.K, cfg.K), dtype=torch.float32, device="cuda")) * 0.01 + torch.eye(cfg.K, device="cuda")
+    zqfp.gptq_pack_weight_fp4(W, U, cfg.G, cfg.mode)
+    torch.cuda.synchronize()
+    a.record()
+    zqfp.gptq_pack_weight_fp4(W, U, cfg.G, cfg.mode)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b)
+    rows.append({"call": "gptq_pack_weight_fp4", "workload": f"{name} K={cfg.K} N={cfg.N} G={cfg.G}",
+                 "ms": round(ms, 3), "tflops_f32": round(float(cfg.K) ** 2 * cfg.N / (ms * 1e-3) / 1e12, 2)})
+    return rows
 
 
 def measured_ceilings():

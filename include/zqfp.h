@@ -257,6 +257,34 @@ int zqfp_lorc_factorize(const void *W, int64_t K, int64_t N, int64_t ldw,
                         void *workspace, void *stream);
 
 /*
+ * gptq_pack_weight_fp4 -- zqfp_pack_weight_fp4 with GPTQ's error feedback (the
+ * weight quantizer of the paper's experiments: Section 3, Appendix A), on the
+ * same E2M1 grid and with the same power-of-two scales (M1 / M2).  Offline
+ * step.  Input channels k = 0, 1, ... are quantized in order; the scaled error
+ * of channel k is pushed onto the channels behind it,
+ *   q_k = S e2m1(w_k / S);  err = (w_k - q_k) / U[k][k];  w_j -= U[k][j] err  (j > k),
+ * where U is the upper Cholesky factor of the inverse Hessian of the layer's
+ * inputs, inv(H) = U^T U.  A group's scale is fixed when its first channel is
+ * reached, from the weights as updated so far; under M2 the column scale is
+ * the ORIGINAL column's absmax / 6.  With H = I the result is the blob of
+ * zqfp_pack_weight_fp4.  Arithmetic is binary32: against a float64 evaluation
+ * a code can differ where an updated weight sits within rounding error of a
+ * grid midpoint.
+ *
+ *   W         [K, N] bfloat16, row stride ldw                          (in)
+ *   Hinv_u    [K, K] float32 row-major, upper triangular               (in)
+ *   G         32, 64, 128 or 256
+ *   packed    zqfp_packed_weight_bytes(K, N, G) bytes, 256-byte aligned (out)
+ *   workspace zqfp_gptq_workspace_bytes(K, N, G) bytes of device memory,
+ *             256-byte aligned (a float32 working copy of W and one block
+ *             of errors)
+ */
+size_t zqfp_gptq_workspace_bytes(int64_t K, int64_t N, int G);
+int zqfp_gptq_pack_weight_fp4(const void *W, int64_t K, int64_t N, int64_t ldw,
+                              const float *Hinv_u, int G, int mode,
+                              void *packed, void *workspace, void *stream);
+
+/*
  * unpack_codes -- canonical view of a packed blob, for bit-exact comparison
  * and inspection (same K, N, G as at packing time).
  *   codes    [K, N] uint8, one E2M1 code (0..15, bit 3 = sign) per byte  (out)

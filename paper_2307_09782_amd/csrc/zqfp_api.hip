@@ -48,7 +48,7 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
 
 extern "C" {
 
-int zqfp_version(void) { return 104; }
+int zqfp_version(void) { return 105; }
 
 const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
 
@@ -202,6 +202,28 @@ int zqfp_lorc_factorize(const void* W, int64_t K, int64_t N, int64_t ldw, const 
     hipError_t e = zqfp::launch_lorc_factorize(static_cast<const uint16_t*>(W), ldw, static_cast<const uint8_t*>(packed), L, r,
                                                Omega, power_iters, static_cast<uint16_t*>(U), static_cast<uint16_t*>(V),
                                                sigma, workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+size_t zqfp_gptq_workspace_bytes(int64_t K, int64_t N, int G)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L) || N == 0 || (G != 32 && G != 64 && G != 128 && G != 256)) return 0;
+    return zqfp::gptq_workspace_bytes(K, N, G);
+}
+
+int zqfp_gptq_pack_weight_fp4(const void* W, int64_t K, int64_t N, int64_t ldw, const float* Hinv_u, int G, int mode,
+                              void* packed, void* workspace, void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L) || N == 0 || ldw < N) return ZQFP_E_SHAPE;
+    if (G != 32 && G != 64 && G != 128 && G != 256) return ZQFP_E_SHAPE;
+    if (mode != ZQFP_SCALE_M1 && mode != ZQFP_SCALE_M2) return ZQFP_E_MODE;
+    if (!W || !Hinv_u || !packed || !workspace) return ZQFP_E_NULL;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0 || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return ZQFP_E_ALIGN;
+    hipError_t e = zqfp::launch_gptq_pack(static_cast<const uint16_t*>(W), ldw, L, mode, Hinv_u, static_cast<uint8_t*>(packed),
+                                          workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 

@@ -196,6 +196,10 @@ size_t lorc_workspace_bytes(int64_t K, int64_t N, int r);
 hipError_t launch_lorc_factorize(const uint16_t* W, int64_t ldw, const uint8_t* blob, const BlobLayout& L, int r,
                                  const float* Omega, int power_iters, uint16_t* U, uint16_t* V, float* sigma,
                                  void* workspace, hipStream_t s);
+// GPTQ with the E2M1 grid (offline): U = upper Cholesky factor of the inverse Hessian, [K][K] float32; G in {32, 64, 128, 256}
+size_t gptq_workspace_bytes(int64_t K, int64_t N, int G);
+hipError_t launch_gptq_pack(const uint16_t* W, int64_t ldw, const BlobLayout& L, int mode, const float* U, uint8_t* blob,
+                            void* workspace, hipStream_t s);
 hipError_t launch_probe_read(const void* src, int64_t bytes, uint32_t* sink, int workgroups, hipStream_t s);
 hipError_t launch_probe_mfma(const uint32_t* operands, float* sink, int iters, int workgroups, hipStream_t s);
 

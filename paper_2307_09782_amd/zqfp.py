@@ -71,6 +71,10 @@ def lib():
         L.zqfp_lorc_workspace_bytes.argtypes = [i64, i64, c.c_int]
         L.zqfp_lorc_factorize.restype = c.c_int
         L.zqfp_lorc_factorize.argtypes = [p, i64, i64, i64, p, c.c_int, c.c_int, p, c.c_int, p, p, p, p, p]
+        L.zqfp_gptq_workspace_bytes.restype = c.c_size_t
+        L.zqfp_gptq_workspace_bytes.argtypes = [i64, i64, c.c_int]
+        L.zqfp_gptq_pack_weight_fp4.restype = c.c_int
+        L.zqfp_gptq_pack_weight_fp4.argtypes = [p, i64, i64, i64, p, c.c_int, c.c_int, p, p, p]
         L.zqfp_probe_stream_read.restype = c.c_int
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
         L.zqfp_probe_mfma.restype = c.c_int
@@ -274,6 +278,25 @@ def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=AC
     _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
                                      Y.stride(0), code, accum, _ptr(ws), _stream(Xq)))
     return Y
+
+
+def gptq_pack_weight_fp4(W, Hinv_u, G, mode):
+    """GPTQ on the E2M1 grid: W [K,N] bf16, Hinv_u [K,K] f32 (upper Cholesky factor of the inverse Hessian)
+    -> the packed blob (same format as pack_weight_fp4)."""
+    _rows(W, torch.bfloat16), _dev(Hinv_u, torch.float32, 2)
+    K, N = W.shape
+    if tuple(Hinv_u.shape) != (K, K):
+        raise ZqfpError(-2, "Hinv_u must be [K, K]")
+    nbytes = packed_weight_bytes(K, N, G)
+    wsb = int(lib().zqfp_gptq_workspace_bytes(K, N, G))
+    if nbytes == 0 or wsb == 0:
+        raise ZqfpError(-2, "shape / group size")
+    packed = torch.empty((nbytes,), dtype=torch.uint8, device=W.device)
+    ws = torch.empty((wsb + 256,), dtype=torch.uint8, device=W.device)
+    off = (-ws.data_ptr()) % 256
+    _check(lib().zqfp_gptq_pack_weight_fp4(_ptr(W), K, N, W.stride(0), _ptr(Hinv_u), G, mode, _ptr(packed),
+                                           ws.data_ptr() + off, _stream(W)))
+    return packed
 
 
 def lorc_factorize(W, packed, G, r, Omega, power_iters=2):
