@@ -21,13 +21,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 
-__device__ inline uint16_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
-    return (uint16_t)(u >> 16);
-}
-
 // NW: waves per workgroup (8 or 16); KPW: k-tiles per wave (K / 128 / NW, rounded up); NB: fragment
 // buffers, i.e. NB - 1 strips in flight behind the one being multiplied.  One workgroup per compute
 // unit: NW / 4 waves per SIMD.

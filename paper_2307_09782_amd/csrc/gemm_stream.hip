@@ -26,13 +26,6 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kUnroll = 4;  // k-tiles whose loads are issued before their matrix instructions
 
-__device__ inline uint16_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
-    return (uint16_t)(u >> 16);
-}
-
 template <int MT, bool EXACT>
 __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restrict__ Xq, const float* __restrict__ sx,
                                                         int64_t M, const uint8_t* __restrict__ blob, BlobLayout L,

@@ -34,13 +34,6 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ inline uint16_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 // LDS-direct loads.  Lane l of the wave fetches 16 (or 4) bytes at gbase + voff and the hardware
 // writes them to LDS byte address lds_base + 16 (4) * l; lds_base travels in M0 and is uniform.
 // The compiler knows nothing of these loads or of their LDS writes: they are waited for by hand

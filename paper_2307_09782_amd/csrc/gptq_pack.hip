@@ -14,45 +14,6 @@
 namespace zqfp {
 namespace {
 
-__device__ inline float bf16_bits(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-
-// least integer n with amax <= 6 * 2^n, clamped to [-126, 127]; 0 for a zero group
-__device__ inline int m1_exponent(float amax)
-{
-    if (amax == 0.0f) return 0;
-    const uint32_t b = __float_as_uint(amax);
-    const int ex = (int)(b >> 23);
-    if (ex == 0) return -126;
-    const uint32_t man = b & 0x7FFFFFu;
-    const int n = (ex - 127) - ((man <= 0x400000u) ? 2 : 1);  // significand <= 1.5 ?
-    return min(127, max(-126, n));
-}
-
-// least k >= 0 with amax_max <= amax_g * 2^k, at most 15
-__device__ inline int m2_shift(float amax_max, float amax_g)
-{
-    if (amax_g == 0.0f) return 15;
-    int k = 0;
-    while (k < 15 && amax_max > ldexpf(amax_g, k)) ++k;
-    return k;
-}
-
-// nearest E2M1 magnitude, ties to the even code, saturating at 6; sign bit copied
-__device__ inline uint32_t e2m1_encode(float y)
-{
-    const float a = fabsf(y);
-    const uint32_t c = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u
-                     : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
-    return c | ((__float_as_uint(y) >> 28) & 8u);
-}
-
-__device__ inline float e2m1_value(uint32_t code)
-{
-    const uint32_t mag = code & 7u;
-    const float v = mag < 2u ? 0.5f * (float)mag : (float)(2u + (mag & 1u)) * (float)(1u << ((mag >> 1) - 1u)) * 0.5f;
-    return (code & 8u) ? -v : v;
-}
-
 // Working copy of W in float32, column absmax of the original W, and the blob's frame: header, zero codes,
 // exponent bytes 127, column scales (1 under M1, absmax / 6 under M2, 0 for padding columns).
 __global__ __launch_bounds__(256) void k_gptq_init(const uint16_t* __restrict__ W, int64_t ldw, BlobLayout L, int mode,
@@ -68,7 +29,7 @@ __global__ __launch_bounds__(256) void k_gptq_init(const uint16_t* __restrict__ 
         float mx = 0.0f;
         if (n < L.N)
             for (int64_t k = 0; k < L.K; ++k) {
-                const float w = bf16_bits(W[k * ldw + n]);
+                const float w = bf16_bits_to_f32(W[k * ldw + n]);
                 Wf[k * L.N + n] = w;
                 mx = fmaxf(mx, fabsf(w));
             }

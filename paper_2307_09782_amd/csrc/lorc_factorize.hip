@@ -19,14 +19,6 @@ namespace {
 
 constexpr int kLMax = 72;  // r <= 64 plus 8 columns of oversampling
 
-__device__ inline float e2m1_value(uint32_t code)
-{
-    // sign . 2 exponent bits . 1 mantissa bit, bias 1: 0, 0.5, 1, 1.5, 2, 3, 4, 6
-    const uint32_t mag = code & 7u;
-    const float v = mag < 2u ? 0.5f * (float)mag : (float)(2u + (mag & 1u)) * (float)(1u << ((mag >> 1) - 1u)) * 0.5f;
-    return (code & 8u) ? -v : v;
-}
-
 // E[k][n] = W[k][n] - c[n] * 2^(e - 127) * e2m1(code), one element per thread
 __global__ __launch_bounds__(256) void k_lorc_error(const uint16_t* __restrict__ W, int64_t ldw,
                                                     const uint8_t* __restrict__ blob, BlobLayout L, float* __restrict__ E)

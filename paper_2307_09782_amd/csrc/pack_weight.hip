@@ -14,38 +14,6 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ inline float bf16_bits(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-
-// least integer n with amax <= 6 * 2^n (= ceil(log2(amax / 6))), clamped to [-126, 127]
-__device__ inline int m1_exponent(float amax)
-{
-    if (amax == 0.0f) return 0;
-    uint32_t b = __float_as_uint(amax);
-    int ex = (int)(b >> 23);
-    if (ex == 0) return -126;  // below 2^-126: far under the clamp
-    uint32_t man = b & 0x7FFFFFu;
-    int n = (ex - 127) - ((man <= 0x400000u) ? 2 : 1);  // significand <= 1.5 ?
-    return min(127, max(-126, n));
-}
-
-// least k >= 0 with amax_max <= amax_g * 2^k (= ceil(log2(S_max / S_g))), clamped to 15
-__device__ inline int m2_shift(float amax_max, float amax_g)
-{
-    if (amax_g == 0.0f) return 15;
-    int k = 0;
-    while (k < 15 && amax_max > ldexpf(amax_g, k)) ++k;
-    return k;
-}
-
-// round to nearest E2M1 magnitude, ties to the even code, saturating at 6
-__device__ inline uint32_t e2m1_encode(float y)
-{
-    float a = fabsf(y);
-    uint32_t c = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u
-               : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
-    return c | ((__float_as_uint(y) >> 28) & 8u);
-}
-
 __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __restrict__ W, int64_t ldw, BlobLayout L,
                                                         int mode, uint8_t* __restrict__ blob)
 {
@@ -66,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __rest
         float a = 0.0f;
         if (live)
             for (int64_t k = (int64_t)g * L.G + kl; k < (int64_t)(g + 1) * L.G; k += 16)
-                a = fmaxf(a, fabsf(bf16_bits(W[k * ldw + n])));
+                a = fmaxf(a, fabsf(bf16_bits_to_f32(W[k * ldw + n])));
         s_red[kl * 16 + c] = a;
         __syncthreads();
         if (tid < 16) {
@@ -121,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __rest
         if (fn < L.N) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                float w = bf16_bits(W[(k0 + i) * ldw + fn]);
+                float w = bf16_bits_to_f32(W[(k0 + i) * ldw + fn]);
                 float y = (mode == 1) ? ldexpf(w, -e)        // exact division by 2^e
                                       : ldexpf(w / cs, -e);  // IEEE division, then exact shift
                 word |= e2m1_encode(y) << (4 * i);

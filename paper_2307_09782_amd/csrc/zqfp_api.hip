@@ -44,16 +44,8 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
-}  // namespace
-
-extern "C" {
-
-int zqfp_version(void) { return 105; }
-
-const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
-
 // argument checks shared by the quantizer entry points; `normalised` rows are limited to what registers hold
-static int quantize_common(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r,
+int quantize_common(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U, int r,
                            float* T, const zqfp::Producer& pr, void* stream)
 {
     if (M < 0 || K <= 0 || K % 128 != 0 || ldx < K || r < 0 || r > 64) return ZQFP_E_SHAPE;
@@ -75,7 +67,15 @@ static int quantize_common(const void* X, int64_t M, int64_t K, int64_t ldx, uin
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
-static const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
+const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
+
+}  // namespace
+
+extern "C" {
+
+int zqfp_version(void) { return 105; }
+
+const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
 
 int zqfp_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const void* U,
                           int r, float* T, void* stream)

@@ -75,6 +75,14 @@ inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
     return true;
 }
 
+// binary32 -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ inline uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
 // IEEE binary16 bits -> binary32 (exact)
 __device__ inline float half_bits_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 
@@ -101,6 +109,49 @@ __device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i&
         hi[i] = (int)h;
         lo[i] = (int)l;
     }
+}
+
+// ---------------------------------------------------------------------------
+// E2M1 and scale helpers shared by the weight-side kernels (packer, GPTQ, LoRC error matrix)
+// ---------------------------------------------------------------------------
+__device__ inline float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// least integer n with amax <= 6 * 2^n (= ceil(log2(amax / 6))), clamped to [-126, 127]; 0 for a zero group
+__device__ inline int m1_exponent(float amax)
+{
+    if (amax == 0.0f) return 0;
+    const uint32_t b = __float_as_uint(amax);
+    const int ex = (int)(b >> 23);
+    if (ex == 0) return -126;  // below 2^-126: far under the clamp
+    const uint32_t man = b & 0x7FFFFFu;
+    const int n = (ex - 127) - ((man <= 0x400000u) ? 2 : 1);  // significand <= 1.5 ?
+    return min(127, max(-126, n));
+}
+
+// least k >= 0 with amax_max <= amax_g * 2^k (= ceil(log2(S_max / S_g))), clamped to 15
+__device__ inline int m2_shift(float amax_max, float amax_g)
+{
+    if (amax_g == 0.0f) return 15;
+    int k = 0;
+    while (k < 15 && amax_max > ldexpf(amax_g, k)) ++k;
+    return k;
+}
+
+// round to nearest E2M1 magnitude, ties to the even code, saturating at 6; sign bit copied
+__device__ inline uint32_t e2m1_encode(float y)
+{
+    const float a = fabsf(y);
+    const uint32_t c = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u
+                     : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
+    return c | ((__float_as_uint(y) >> 28) & 8u);
+}
+
+// value of an E2M1 code (sign . 2 exponent bits . 1 mantissa bit, bias 1): 0, 0.5, 1, 1.5, 2, 3, 4, 6
+__device__ inline float e2m1_value(uint32_t code)
+{
+    const uint32_t mag = code & 7u;
+    const float v = mag < 2u ? 0.5f * (float)mag : (float)(2u + (mag & 1u)) * (float)(1u << ((mag >> 1) - 1u)) * 0.5f;
+    return (code & 8u) ? -v : v;
 }
 
 // Tile shape and K-split of the tiled GEMM for a problem size (the launcher and the workspace query
