@@ -14,7 +14,8 @@
 // behind the other's matrix instructions: two of an 8-wave workgroup that has
 // the compute unit to itself (three LDS stages), or one from each of two 4-wave
 // workgroups (two stages each), whose prologues, epilogues and barriers then
-// fall at different times.  A stage
+// fall at different times, or -- small tiles, few of them -- one from each of
+// two wave groups of a workgroup that take the k-tiles in turn.  A stage
 // is filled by LDS-direct loads (global_load_lds_dwordx4: every lane names a
 // 16 B chunk in global memory, the wave's 64 chunks land in one contiguous
 // 1 KB block of LDS), NSTAGE - 1 k-steps ahead of its use: no staging
@@ -95,33 +96,42 @@ __device__ inline void wait_loads_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE_>
+// KG wave groups of WAVES_M x WAVES_N waves share the tile and take the k-tiles in turn (k-tile kt by group
+// kt % KG), each with its own operands in LDS and its own accumulators; the groups' sums meet in LDS in the
+// epilogue.  KG = 2 gives the small tile two waves per SIMD where the tile count leaves one workgroup per
+// compute unit.  GT = threads of one group; the per-group quantities below are written in terms of it.
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE_, int KG_ = 1>
 struct TileCfg {
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int KG = KG_;
+    static constexpr int GT = 64 * WAVES_M * WAVES_N;
+    static constexpr int THREADS = GT * KG;
     static constexpr int BM = WAVES_M * WTM * 16, BN = WAVES_N * WTN * 16;
     static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 64;
-    static constexpr int E_BYTES = THREADS * 4;               // one exponent dword per output channel (first BN used)
-    static constexpr int STAGE = A_BYTES + B_BYTES + E_BYTES;
+    static constexpr int E_BYTES = GT * 4;                    // one exponent dword per output channel (first BN used)
+    static constexpr int SUB = A_BYTES + B_BYTES + E_BYTES;   // one k-tile's operands
+    static constexpr int STAGE = SUB * KG;
     static constexpr int NSTAGE = NSTAGE_;
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the loop keeps NSTAGE - 1 k-tiles in flight behind the one it multiplies");
-    static constexpr int A_CHUNKS = A_BYTES / 16 / THREADS;  // 16 B chunks per thread
-    static constexpr int B_CHUNKS = B_BYTES / 16 / THREADS;
-    static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile / thread mismatch");
-    static_assert(BN <= THREADS, "one exponent dword per thread");
+    static constexpr int A_CHUNKS = A_BYTES / 16 / GT;  // 16 B chunks per thread
+    static constexpr int B_CHUNKS = B_BYTES / 16 / GT;
+    static_assert(A_BYTES % (16 * GT) == 0 && B_BYTES % (16 * GT) == 0, "tile / thread mismatch");
+    static_assert(BN <= GT, "one exponent dword per thread");
+    static_assert(KG == 1 || KG == 2, "one or two wave groups");
     static_assert((NSTAGE - 1) * (A_CHUNKS + B_CHUNKS + 1) <= 63, "outstanding loads must fit the 6-bit load counter");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "stages exceed the LDS of a compute unit");
 };
 
 // Two waves per SIMD in every configuration (8-wave workgroups alone on a compute unit, 4-wave
 // workgroups in pairs): 256 registers per lane.
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, bool EXACT>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
     BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n, int ksplit,
     int kslice, float* __restrict__ partial)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE>;
-    constexpr int kThreads = C::THREADS;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG>;
+    constexpr int kThreads = C::THREADS;  // of the workgroup
+    constexpr int kGT = C::GT;            // of one wave group
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- workgroup -> tile.  Consecutive workgroup ids go to consecutive XCDs (8 of them, one
@@ -147,15 +157,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     const int tm = first_m + (pid % in_group) % gsz;
     const int tn = (pid % in_group) / gsz;
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS block addresses go to M0
+    const int wg_tid = threadIdx.x, lane = wg_tid & 63;
+    const int wg_wave = __builtin_amdgcn_readfirstlane(wg_tid >> 6);  // scalar: LDS block addresses go to M0
+    const int kgrp = KG == 1 ? 0 : wg_wave / (kGT / 64);             // this wave's group: k-tiles kgrp, kgrp + KG, ...
+    const int wave = wg_wave - kgrp * (kGT / 64), tid = wg_tid - kgrp * kGT;  // inside the group
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int col = lane & 15, lb = lane >> 4;
     const int64_t m0 = (int64_t)tm * C::BM;
     const int64_t strip0 = (int64_t)tn * (C::BN / 16);
     const int nkt_all = (int)L.nkt;                 // k-tiles of the whole K (the packed layout's stride)
-    const int kt0 = slice * kslice;                 // this workgroup's first k-tile
-    const int nkt = min(kslice, nkt_all - kt0);     // and how many it multiplies (>= 1)
+    const int kt_first = slice * kslice;            // this workgroup's first k-tile
+    const int nkt_wg = min(kslice, nkt_all - kt_first);  // and how many it multiplies (>= 1; a multiple of KG: the launcher's duty)
+    const int kt0 = kt_first + kgrp;                // this wave group's first k-tile; its local step kt is k-tile kt0 + KG * kt
+    const int nkt = nkt_wg / KG;                    // steps of every group
 
     // ---- load addresses: uniform base pointers plus 32-bit per-lane offsets.  Rows past M
     // and strips past the last one are clamped to the last valid one: what they produce is
@@ -172,13 +186,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     uint32_t a_off[C::A_CHUNKS], b_off[C::B_CHUNKS];
 #pragma unroll
     for (int i = 0; i < C::A_CHUNKS; ++i) {
-        const int row = (wave + (kThreads / 64) * i) * 8 + (lane >> 3);
+        const int row = (wave + (kGT / 64) * i) * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ (row & 7);
         a_off[i] = (uint32_t)(min(row, rows_here - 1) * (int)L.K + 16 * chunk);
     }
 #pragma unroll
     for (int i = 0; i < C::B_CHUNKS; ++i) {
-        const int cidx = tid + kThreads * i;
+        const int cidx = tid + kGT * i;
         const int64_t strip = min(strip0 + (cidx >> 6), L.nstrips - 1);
         b_off[i] = (uint32_t)((strip * nkt_all * 64 + (cidx & 63)) * 16);
     }
@@ -186,7 +200,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // t % BN of the tile; it lands in LDS as [column] and every lane later picks its own.
     const uint32_t e_off = 4u * ((uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15));
     // LDS byte addresses (the dynamic array is the kernel's only LDS object)
-    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem + kgrp * C::SUB;  // the group's share of a stage
     const uint32_t a_dst = lds0 + wave * 1024;
     const uint32_t b_dst = lds0 + C::A_BYTES + wave * 1024;
     const uint32_t e_dst = lds0 + C::A_BYTES + C::B_BYTES + wave * 256;
@@ -201,11 +215,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     auto group_of = [&](const GroupCursor& c, int kt, int b) {
         return small_groups ? ((kt * 4 + b) >> L.gsb_shift) : c.g;
     };
-    auto advance = [&](GroupCursor& c) {
-        const int sub = c.sub + 1;
-        const bool wrap = sub == gq;
-        c.sub = wrap ? 0 : sub;
-        c.g += wrap ? 1 : 0;
+    auto advance = [&](GroupCursor& c) {  // to the group's next k-tile, KG k-tiles further on
+#pragma unroll
+        for (int q = 0; q < KG; ++q) {
+            const int sub = c.sub + 1;
+            const bool wrap = sub == gq;
+            c.sub = wrap ? 0 : sub;
+            c.g += wrap ? 1 : 0;
+        }
     };
 
     // ---- one stage = NSIDE loads per wave: A_CHUNKS + B_CHUNKS 1 KB blocks and 256 B of exponents
@@ -213,11 +230,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     // t-th load of k-tile kt into LDS stage `stage`
     auto side_load = [&](int t, int kt, int stage, const GroupCursor& c) __attribute__((always_inline)) {
         const uint32_t st = (uint32_t)stage * C::STAGE;
-        if (t < C::A_CHUNKS) lds_load16(a_base + (kt0 + kt) * 128, a_off[t], st + a_dst + t * (kThreads / 64) * 1024);
+        if (t < C::A_CHUNKS) lds_load16(a_base + (kt0 + KG * kt) * 128, a_off[t], st + a_dst + t * (kGT / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            lds_load16(b_base + (int64_t)(kt0 + kt) * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kThreads / 64) * 1024);
+            lds_load16(b_base + (int64_t)(kt0 + KG * kt) * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kGT / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
-            lds_load4(e_base + (group_of(c, kt0 + kt, 0) >> 2) * 64, e_off, st + e_dst);
+            lds_load4(e_base + __builtin_amdgcn_readfirstlane((group_of(c, kt0 + KG * kt, 0) >> 2) * 64), e_off, st + e_dst);
     };
 
     v4f acc[WTM][WTN];
@@ -276,7 +293,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
         constexpr bool fetch = !last_block || NEXT;
         v8i& cur = (I & 1) ? fz : fy;
         v8i& inc = (I & 1) ? fy : fz;
-        const int esh = 8 * (group_of(cur_comp, kt0 + kt, lb) & 3);  // this lane's exponent byte: (stored group & 3) of the dword
+        const int esh = 8 * (group_of(cur_comp, kt0 + KG * kt, lb) & 3);  // this lane's exponent byte: (stored group & 3) of the dword
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, PASSES>([&](auto p_tag) __attribute__((always_inline)) {
             constexpr int P = decltype(p_tag)::value;
@@ -413,6 +430,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     constexpr int SLAB_N = 16 * WTN, SLAB_LD = SLAB_N + 4;
     static_assert(C::THREADS / 64 * 16 * SLAB_LD * 4 <= C::NSTAGE * C::STAGE, "epilogue patch does not fit the stages");
     __syncthreads();  // every wave is done reading the stages
+    if constexpr (KG == 2) {  // the second wave group hands its sums over: acc = group 0 + group 1, a fixed order
+        static_assert(WTM * WTN * kGT * 16 <= C::NSTAGE * C::STAGE, "hand-over area does not fit the stages");
+        v4f* comb = reinterpret_cast<v4f*>(smem);
+        if (kgrp == 1) {
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int j = 0; j < WTN; ++j) comb[(i * WTN + j) * kGT + tid] = acc[i][j];
+        }
+        __syncthreads();
+        if (kgrp == 0) {
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int j = 0; j < WTN; ++j) acc[i][j] += comb[(i * WTN + j) * kGT + tid];
+        }
+        __syncthreads();  // the area is reused below
+    }
     float* patch = reinterpret_cast<float*>(smem) + wave * (16 * SLAB_LD);
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
     const int64_t n_wave = (strip0 + wn * WTN) * 16;
@@ -438,17 +473,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves
     const int rk = raw ? 0 : lorc.r;
     const bool lorc_lds = rk > 0 && rk <= RL;
     if (lorc_lds) {
-        for (int idx = tid; idx < C::BM * RL; idx += kThreads) {
+        for (int idx = wg_tid; idx < C::BM * RL; idx += kThreads) {
             const int row = idx / RL, q = idx % RL;
             Ts[idx] = q < rk ? lorc.T[min(m0 + row, M - 1) * rk + q] : 0.f;
         }
-        for (int idx = tid; idx < RL * C::BN; idx += kThreads) {
+        for (int idx = wg_tid; idx < RL * C::BN; idx += kThreads) {
             const int q = idx / C::BN, c = idx % C::BN;
             const int64_t n = min(strip0 * 16 + c, L.N - 1);
             Vs[c * RL + q] = q < rk ? half_bits_to_f32(lorc.V[(int64_t)q * L.N + n]) : 0.f;
         }
         __syncthreads();
     }
+    if (KG == 2 && kgrp != 0) return;  // no barrier below: the first group alone writes the tile out
     constexpr int LPR = SLAB_N / 4;   // lanes per slab row when each lane carries 4 columns
     constexpr int RPI = 64 / LPR;     // slab rows per store instruction
     const int srow = lane / LPR, scol = (lane % LPR) * 4;
@@ -547,16 +583,16 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
     }
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                       void* Y, int64_t ldy, int out_dtype, int ksplit, int kslice, float* partial, hipStream_t s)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG>;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
     const int units = tiles_m * tiles_n * ksplit;
     const int per = (units + 7) / 8;
     const size_t smem = C::NSTAGE * C::STAGE;
-    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, EXACT>;
+    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, EXACT>;
     static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -579,10 +615,27 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
     if (workspace == nullptr) { p.ksplit = 1; p.kslice = (int)L.nkt; }  // no room for partial tiles: one slice
     float* ws = static_cast<float*>(workspace);
     if (p.bm == 128 && p.bn == 256)
-        return launch_cfg<4, 8, 2, 2, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    return launch_cfg<2, 4, 2, 2, 3, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
+        return launch_cfg<4, 8, 2, 2, 2, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
+    // at most one workgroup per compute unit: two wave groups per workgroup take the k-tiles in turn (two waves
+    // per SIMD instead of one; 9-12 % faster at LLaMA-70B FFN M = 32, 64), which needs an even number of them in
+    // every slice.  With more workgroups than compute units the one-group form runs up to three per compute
+    // unit and is the faster one.
+    const int64_t tiles = ((M + 63) / 64) * ((L.Np + 127) / 128);
+    if (p.ksplit >= 2) {  // half as many slices (of even length), two wave groups each: half the partial tiles to add up
+        const int want = (p.ksplit + 1) / 2;
+        int kslice = (int)((L.nkt + want - 1) / want);
+        kslice += kslice & 1;
+        const int ksplit = (int)((L.nkt + kslice - 1) / kslice);
+        const int tail = (int)L.nkt - (ksplit - 1) * kslice;
+        if (tiles * ksplit <= 256 && tail > 0 && tail % 2 == 0) { p.ksplit = ksplit; p.kslice = kslice; }
+    }
+    const int64_t units = tiles * p.ksplit;
+    const int last = (int)L.nkt - (p.ksplit - 1) * p.kslice;
+    if (units <= 256 && p.kslice % 2 == 0 && last % 2 == 0)
+        return launch_cfg<2, 4, 2, 2, 3, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
+    return launch_cfg<2, 4, 2, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
 }
 
 }  // namespace
