@@ -110,3 +110,12 @@ def test_workspace_query_is_pure_host_logic():
     assert ws(100, 3072, 136) == 3 * 100 * 144 * 4        # Np = 144
     assert ws(16, 28672, 8192) == 4 * 16 * 8192 * 4       # decode form: 224 k-tiles in 4 chunks
     assert ws(8, 8192, 4096) == 0 and ws(0, 4096, 4096) == 0 and ws(64, 4100, 4096) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU: `bench.py --gpus 2` exits with a message before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
