@@ -177,7 +177,12 @@ inline TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
     const int64_t n256 = tiles(256, 256);
     if (n256 >= kCUs * 3 / 2) { p.bm = 128; p.bn = 256; return p; }
     if (n256 <= kCUs && n256 * 4 >= kCUs * 3) { p.bm = 256; p.bn = 256; return p; }
-    if (M > 64 && tiles(128, 128) >= 384) { p.bm = 128; p.bn = 128; return p; }
+    // 128 x 128 tiles run two workgroups per compute unit (rounds of 512 tiles), 64 x 128 tiles three (rounds of
+    // 768): up to a round and a half of the small tiles they are the faster ones (7B QKV at M = 512, 768: 9 and 7 %),
+    // unless their last round would be nearly empty or the larger tiles come out as whole rounds
+    const int64_t t128 = tiles(128, 128), t64 = tiles(64, 128);
+    const bool small_fit = t64 <= 1152 && (t64 % 768 == 0 || t64 % 768 >= 256) && t128 % 512 != 0;
+    if (M > 64 && t128 >= 384 && !small_fit) { p.bm = 128; p.bn = 128; return p; }
     const int64_t slots = 2 * kCUs, nt = tiles(64, 128);
     int64_t want = slots / nt;
     if (want > 16) want = 16;
