@@ -236,6 +236,21 @@ def test_gemm_zero_rows_and_signed_zeros():
     check_gemm(Y, Y_o, Sabs + 1e-300)
 
 
+@pytest.mark.parametrize("M,K,N", [(16, 2048, 512), (200, 2048, 512)])
+def test_gemm_on_post_relu_activations(M, K, N):
+    """The fc2-like input of Section 3's observation (2): half the values exactly zero, the rest one-sided, plus
+    outlier channels.  Quantized through the fused ReLU entry point, multiplied in both GEMM forms."""
+    cfg = inputs.Config("relu", K, N, (M,), 128, 1, 0.01, 0, 20.0, 0, 77)
+    X = inputs.make_x(cfg, M)
+    Xr = oracle.relu_bf16(X)
+    Y, Y_o, Sabs = _gemm_case(M, K, N, 128, 1, 0, x_override=Xr)
+    check_gemm(Y, Y_o, Sabs + 1e-300, f"post-ReLU M{M}")
+    Xq, sx = zqfp.relu_quantize_act_fp8(bf16_tensor(X))
+    Xq_o, sx_o = oracle.quantize_act(Xr)
+    assert np.array_equal(_sync_np(Xq), Xq_o) and bits_equal_f32(_sync_np(sx), sx_o)
+    assert (Xq_o == 0).mean() > 0.4
+
+
 FULL = [
     ("opt1p3b_fc1", 2048), ("llama7b_qkv", 1), ("llama7b_qkv", 16), ("llama7b_qkv", 256), ("llama7b_qkv", 4096),
     ("llama7b_ffn_up", 1), ("llama7b_ffn_up", 16), ("llama7b_ffn_up", 256), ("llama7b_ffn_up", 4096),
