@@ -96,6 +96,16 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
     return u >> 16;
 }
 
+// two binary32 values -> two bf16 in one dword (round to nearest even): the packed hardware conversion
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf16_rne(float lo, float hi)
+{
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+
 // 8 bf16 -> 8 bf16: (x * rstd) * g, each product one binary32 operation, rounded to bf16
 __device__ inline uint4 normalize8(uint4 v, uint4 g, float rstd)
 {
@@ -104,7 +114,7 @@ __device__ inline uint4 normalize8(uint4 v, uint4 g, float rstd)
     for (int i = 0; i < 4; ++i) {
         const float lo = (bf16_lo(w[i]) * rstd) * bf16_lo(gw[i]);
         const float hi = (bf16_hi(w[i]) * rstd) * bf16_hi(gw[i]);
-        o[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+        o[i] = pack_bf16_rne(lo, hi);
     }
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
@@ -121,7 +131,7 @@ __device__ inline uint4 normalize8_affine(uint4 v, uint4 g, uint4 b, float mu, f
         const float al = dl * rstd, ah = dh * rstd;
         const float cl = al * bf16_lo(gw[i]), ch = ah * bf16_hi(gw[i]);
         const float lo = cl + bf16_lo(bw[i]), hi = ch + bf16_hi(bw[i]);
-        o[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+        o[i] = pack_bf16_rne(lo, hi);
     }
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
@@ -132,7 +142,7 @@ __device__ inline uint4 add8(uint4 x, uint4 r)
     uint32_t xw[4] = {x.x, x.y, x.z, x.w}, rw[4] = {r.x, r.y, r.z, r.w}, o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        o[i] = f32_to_bf16_rne(bf16_lo(xw[i]) + bf16_lo(rw[i])) | (f32_to_bf16_rne(bf16_hi(xw[i]) + bf16_hi(rw[i])) << 16);
+        o[i] = pack_bf16_rne(bf16_lo(xw[i]) + bf16_lo(rw[i]), bf16_hi(xw[i]) + bf16_hi(rw[i]));
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
@@ -147,18 +157,18 @@ __device__ inline uint4 relu8(uint4 x)
 }
 
 // silu(g) * u in binary64 (g / (1 + exp(-g)) * u), rounded to binary32 and from there to bf16
-__device__ inline uint32_t swiglu1(float g, float u)
+__device__ inline float swiglu1(float g, float u)
 {
     const double gd = (double)g;
     const double t = gd / (1.0 + exp(-gd)) * (double)u;
-    return f32_to_bf16_rne((float)t);
+    return (float)t;
 }
 __device__ inline uint4 swiglu8(uint4 g, uint4 u)
 {
     uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w}, o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        o[i] = swiglu1(bf16_lo(gw[i]), bf16_lo(uw[i])) | (swiglu1(bf16_hi(gw[i]), bf16_hi(uw[i])) << 16);
+        o[i] = pack_bf16_rne(swiglu1(bf16_lo(gw[i]), bf16_lo(uw[i])), swiglu1(bf16_hi(gw[i]), bf16_hi(uw[i])));
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
