@@ -392,10 +392,12 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
 // the reductions are wave shuffles only, and no barrier or LDS is involved; 16 waves per compute
 // unit keep 8 * MAXC KB of loads in flight each.
 // ---------------------------------------------------------------------------
-template <int MAXC, int NORM>
+// LORC: the rank-8 left factor T = y . U rides along; the four waves of a workgroup walk U in step, so three
+// of them are served by the vector cache.
+template <int MAXC, int NORM, bool LORC>
 __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
                                                      uint8_t* __restrict__ Xq, float* __restrict__ sx,
-                                                     Producer pr)
+                                                     const uint16_t* __restrict__ U, float* __restrict__ T, Producer pr)
 {
     const uint16_t* __restrict__ gain = pr.gain;
     const uint16_t* __restrict__ bias = pr.bias;
@@ -461,6 +463,35 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
             }
         }
     }
+    float acc[8];
+    if constexpr (LORC) {  // first, so that the loads of U are in flight during the absmax reduction
+        // A lane holds 8 consecutive elements; it trades them, through the wave's own 1 KB of LDS, for elements
+        // lane, lane + 64, ... of the chunk's 512, so that one load instruction of the wave covers 64
+        // consecutive rows of U (1 KB contiguous) instead of 64 separate lines.
+        __shared__ __attribute__((aligned(16))) uint16_t s_x[4][512];
+        const int wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+        const uint4* u4 = reinterpret_cast<const uint4*>(U);  // row k of U (8 binary16 values) is u4[k]
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            if (c * 64 < nchunk) {  // the same for the whole wave
+                *reinterpret_cast<uint4*>(&s_x[wave][lane * 8]) = v[c];  // same wave writes and reads: no barrier
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float x = __uint_as_float((uint32_t)s_x[wave][lane + 64 * i] << 16);
+                    const int64_t k = (int64_t)c * 512 + 64 * i + lane;
+                    const uint4 u = u4[k < K ? k : K - 1];  // past the row's end x is zero
+                    const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc[2 * q] = fmaf(x, half_bits_to_float(uw[q] & 0xFFFFu), acc[2 * q]);
+                        acc[2 * q + 1] = fmaf(x, half_bits_to_float(uw[q] >> 16), acc[2 * q + 1]);
+                    }
+                }
+            }
+        }
+    }
     uint32_t am = 0;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) am = absmax_bits(am, v[c]);
@@ -478,6 +509,15 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
         const int idx = c * 64 + lane;
         if (idx < nchunk) qrow[idx] = encode8(v[c], inv);
     }
+    if constexpr (LORC) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float a = acc[j];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off);
+            if (lane == 0) T[row * 8 + j] = a;
+        }
+    }
 }
 
 }  // namespace
@@ -487,10 +527,15 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
 {
     if (M == 0) return hipSuccess;
     const int kind = pr.kind;
-    if (r == 0 && M >= 1024 && K <= 8192) {  // many tokens, no LoRC factor: one wave per token
+    // many tokens, no LoRC factor: one wave per token; so too with the rank-8 factor on rows of more than 4096
+    // elements (measured: 6-10 % faster there, slower on shorter rows)
+    if (M >= 1024 && K <= 8192 && (r == 0 || (r == 8 && K > 4096))) {
         const dim3 g4((unsigned)((M + 3) / 4));
-#define ZQ_ROWS_N(MAXC, KIND) \
-    hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, pr)
+#define ZQ_ROWS_N(MAXC, KIND)                                                                                               \
+    do {                                                                                                                    \
+        if (r == 8) hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND, true>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, U, T, pr);  \
+        else hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND, false>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, U, T, pr);        \
+    } while (0)
 #define ZQ_ROWS(MAXC)                          \
     do {                                       \
         switch (kind) {                        \

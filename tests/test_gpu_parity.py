@@ -72,7 +72,11 @@ def test_quantizer_edge_rows_and_long_rows():
 
 
 @pytest.mark.parametrize("name,M,r", [("tiny", 16, 8), ("llama13b_ffn_lorc", 16, 8), ("llama70b_ffn_decode", 4, 8),
-                                      ("tiny", 5, 3), ("tiny", 7, 16), ("tiny", 3, 40)])
+                                      ("tiny", 5, 3), ("tiny", 7, 16), ("tiny", 3, 40),
+                                      # many tokens: the wave-per-token kernel carries the rank-8 factor (K = 256 ... 8192);
+                                      # other ranks stay with the workgroup-per-token kernel
+                                      ("llama13b_ffn_lorc", 1100, 8), ("llama70b_ffn_decode", 1030, 8), ("tiny", 1025, 8),
+                                      ("opt1p3b_fc1", 1024, 8), ("llama7b_qkv", 1027, 16), ("llama7b_qkv", 1500, 5)])
 def test_lorc_left_factor(name, M, r):
     cfg = CFG[name]
     X = inputs.make_x(cfg, M)
@@ -473,6 +477,7 @@ def _producer_case(K, M, rank, seed):
 
 
 PRODUCER_SHAPES = [(256, 16, 0), (2048, 300, 0), (4096, 77, 8), (8192, 1030, 0), (4096, 1100, 0), (2048, 1027, 0),
+                   (4096, 1100, 8), (8192, 1025, 8), (5120, 1024, 8),
                    (11008, 40, 8), (28672, 3, 0), (32768, 2, 0), (128, 9, 0), (8320, 70, 8)]
 
 
