@@ -362,7 +362,7 @@ def main():
     copies = 1
     if decode:  # HBM-bound: rotate through weight copies that together exceed the 256 MB last-level cache
         cfg0 = inputs.CONFIGS[args.workload]
-        copies = max(1, -(-600_000_000 // (cfg0.K * cfg0.N // 2)))
+        copies = min(64, max(1, -(-600_000_000 // (cfg0.K * cfg0.N // 2))))
     main_wl = Workload(args.workload, args.M, accum, copies)
     ms, gemm_ms = main_wl.run(args.steps, args.warmup)
     cfg = main_wl.cfg
@@ -373,7 +373,7 @@ def main():
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4),
                     "traffic": measured_traffic(f"{args.workload} M={args.M} {args.accum}"),
-                    "kernel": "k_gemm_decode" if args.M <= 16 else "k_gemm_stream", "kernel_ms": round(gemm_ms, 5),
+                    "kernel": "k_gemm_decode" if args.M <= 16 else "k_gemm_tile", "kernel_ms": round(gemm_ms, 5),
                     "weight_copies_rotated": copies}
     else:
         gemm_tflops = main_wl.flops / (gemm_ms * 1e-3) / 1e12
