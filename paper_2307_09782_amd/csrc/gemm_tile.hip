@@ -271,7 +271,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         frag[d] = (int)l;
     };
     constexpr int PASSES = EXACT ? 2 : 1;
-    static_assert(WTM % 2 == 0 && 8 % WTN == 0 && WTN >= 4, "fragment rotation, split slots and wait schedule assume these");
+    static_assert(WTM % 2 == 0 && WTN >= 4 && WTN <= 8, "fragment rotation, split slots and wait schedule assume these");
 
     // ---- one row block of a k-step: WTN (x2 in the exact mode) matrix instructions on row block I
     // of k-tile kt, whose stage starts at LDS offset st.  In-order issue means that whatever a
@@ -486,8 +486,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     }
     if (KG == 2 && kgrp != 0) return;  // no barrier below: the first group alone writes the tile out
     constexpr int LPR = SLAB_N / 4;   // lanes per slab row when each lane carries 4 columns
-    constexpr int RPI = 64 / LPR;     // slab rows per store instruction
+    constexpr int RPI = 64 / LPR;     // slab rows per store instruction (lanes beyond RPI * LPR idle when 64 % LPR != 0)
+    static_assert(RPI >= 1 && 16 % RPI == 0, "slab rows per store instruction");
     const int srow = lane / LPR, scol = (lane % LPR) * 4;
+    const bool lane_stores = lane < RPI * LPR;
     const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
@@ -527,10 +529,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         }
 #pragma unroll
         for (int t = 0; t < 16 / RPI; ++t) {
-            const int r = t * RPI + srow;
+            const int r = lane_stores ? t * RPI + srow : 0;
             const v4f y = *reinterpret_cast<const v4f*>(patch + r * SLAB_LD + scol);
             const int64_t m = m_slab + r, n = n_wave + scol;
-            if (m >= M || n >= L.N) continue;
+            if (!lane_stores || m >= M || n >= L.N) continue;
             if (out_dtype == 0) {
                 float* dst = reinterpret_cast<float*>(Y) + m * ldy + n;
                 if (vec_ok && n + 3 < L.N) {
@@ -614,6 +616,8 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
     TilePlan p = plan_tiles(M, L.Np, L.nkt);
     if (workspace == nullptr) { p.ksplit = 1; p.kslice = (int)L.nkt; }  // no room for partial tiles: one slice
     float* ws = static_cast<float*>(workspace);
+    if (p.bm == 128 && p.bn == 192)
+        return launch_cfg<4, 6, 2, 2, 2, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
     if (p.bm == 128 && p.bn == 256)
         return launch_cfg<4, 8, 2, 2, 2, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
     if (p.bm == 256) return launch_cfg<4, 8, 4, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);

@@ -256,7 +256,8 @@ def test_gemm_on_post_relu_activations(M, K, N):
 
 
 FULL = [
-    ("opt1p3b_fc1", 2048), ("llama7b_qkv", 1), ("llama7b_qkv", 16), ("llama7b_qkv", 256), ("llama7b_qkv", 4096),
+    ("opt1p3b_fc1", 2048), ("llama7b_qkv", 1000),  # M = 1000: 128 x 192 tiles with a ragged last row block
+    ("llama7b_qkv", 1), ("llama7b_qkv", 16), ("llama7b_qkv", 256), ("llama7b_qkv", 4096),
     ("llama7b_ffn_up", 1), ("llama7b_ffn_up", 16), ("llama7b_ffn_up", 256), ("llama7b_ffn_up", 4096),
     ("llama13b_ffn_lorc", 16), ("llama13b_ffn_lorc", 2048),
     ("llama70b_ffn_decode", 1), ("llama70b_ffn_decode", 4), ("llama70b_ffn_decode", 16), ("llama70b_ffn_decode", 64),
@@ -265,6 +266,15 @@ FULL = [
     ("llama70b_ffn_down", 1), ("llama70b_ffn_down", 16), ("llama70b_ffn_down", 64),
     ("llama7b_attn_out", 16), ("llama7b_attn_out", 4096),
 ]
+
+
+@pytest.mark.parametrize("M,K,N,G,mode,r", [(1024, 1024, 12200, 128, 2, 8), (960, 256, 12288, 64, 1, 0),
+                                         (1000, 384, 12280, 128, 1, 3)])
+def test_gemm_tiles_of_192_columns_sampled_outputs(M, K, N, G, mode, r):
+    """Shapes the planner gives 128 x 192 tiles (a single round that 256 x 256 tiles would leave partly idle):
+    ragged last row block, ragged last column tile, LoRC in the epilogue, both scale methods."""
+    Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r, full=False)
+    check_gemm(Y, Y_o, Sabs, f"192-column tiles M{M} K{K} N{N}")
 
 
 @pytest.mark.parametrize("name,M", FULL)
