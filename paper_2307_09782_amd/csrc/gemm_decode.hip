@@ -292,6 +292,8 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
     else if (len <= 16) e = launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 32) e = launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 40) e = launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 48) e = launch_kpw<8, 6, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 56) e = launch_kpw<8, 7, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else e = launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     if (e != hipSuccess || nch == 1) return e;
     return launch_splitk_reduce(partial, nch, M, blob, L, sx, lorc, Y, ldy, out_dtype, s);

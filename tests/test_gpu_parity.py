@@ -200,6 +200,8 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (7, 512, 48, 128, 2, 16),       # decode form, rank too large for registers: read in place
     (16, 8192, 80, 128, 1, 8),      # decode form, 64 k-tiles (8 per wave) with LoRC
     (3, 5120, 96, 128, 2, 5),       # decode form, 40 k-tiles (5 per wave)
+    (11, 5888, 112, 128, 1, 8),     # decode form, 46 k-tiles (6 per wave, the last two waves one fewer)
+    (16, 7168, 64, 64, 2, 4),       # decode form, 56 k-tiles (7 per wave), groups of 64
     (17, 384, 72, 128, 1, 0),       # smallest M of the tiled form (64 x 128 tiles), N not a multiple of 16
     (64, 2048, 200, 256, 2, 8),     # 64 x 128 tiles, 16 k-steps, groups of 256, LoRC staged in LDS
     (48, 128, 64, 32, 1, 2),        # a single k-step (no load pipeline to speak of), groups of 32
@@ -590,7 +592,8 @@ def test_gemm_k_split_is_optional_and_agrees_with_the_unsplit_launch():
 
 
 @pytest.mark.parametrize("M,K,N,G,mode,r", [(16, 8320, 8192, 64, 2, 8),     # 65 k-tiles: chunks of 33 and 32
-                                            (5, 16640, 5504, 128, 1, 0)])   # 130 k-tiles: three chunks of 44, 44, 42
+                                            (5, 16640, 5504, 128, 1, 0),    # 130 k-tiles: three chunks of 44, 44, 42
+                                            (7, 14080, 8192, 128, 1, 8)])   # 110 k-tiles: two chunks of 55
 def test_gemm_decode_long_k_in_chunks(M, K, N, G, mode, r):
     """Decode form with more than 64 k-tiles and strips enough for the chunked path (partial sums
     through the workspace, scales and LoRC in the reduce kernel); sampled outputs."""
