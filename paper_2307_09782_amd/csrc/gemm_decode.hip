@@ -290,6 +290,7 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
     hipError_t e;
     if (len <= 8) e = launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 16) e = launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    else if (len <= 24) e = launch_kpw<8, 3, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 32) e = launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 40) e = launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
     else if (len <= 48) e = launch_kpw<8, 6, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);

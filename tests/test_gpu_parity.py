@@ -200,6 +200,7 @@ def _gemm_case(M, K, N, G, mode, r=0, seed_cfg="tiny", full=True, nsamples=4096,
     (7, 512, 48, 128, 2, 16),       # decode form, rank too large for registers: read in place
     (16, 8192, 80, 128, 1, 8),      # decode form, 64 k-tiles (8 per wave) with LoRC
     (3, 5120, 96, 128, 2, 5),       # decode form, 40 k-tiles (5 per wave)
+    (9, 2560, 176, 128, 1, 8),      # decode form, 20 k-tiles (3 per wave, the last four waves one fewer)
     (11, 5888, 112, 128, 1, 8),     # decode form, 46 k-tiles (6 per wave, the last two waves one fewer)
     (16, 7168, 64, 64, 2, 4),       # decode form, 56 k-tiles (7 per wave), groups of 64
     (17, 384, 72, 128, 1, 0),       # smallest M of the tiled form (64 x 128 tiles), N not a multiple of 16
