@@ -193,11 +193,13 @@ int zqfp_relu_quantize_act_fp8(const void *X, int64_t M, int64_t K, int64_t ldx,
  *
  *   G    [M, K] bfloat16, row stride ldg (the gate projection's output)  (in)
  *   Up   [M, K] bfloat16, row stride ldu (the up projection's output)    (in)
+ *   H    [M, K] bfloat16, dense, 16-byte aligned: y itself, for a caller
+ *        that wants the unquantized activation too; may be NULL        (out)
  * K <= 32768; alignment, other arguments and errors as for
  * zqfp_quantize_act_fp8 (T = y.U).
  */
 int zqfp_swiglu_quantize_act_fp8(const void *G, const void *Up, int64_t ldu,
-                                 int64_t M, int64_t K, int64_t ldg,
+                                 void *H, int64_t M, int64_t K, int64_t ldg,
                                  uint8_t *Xq, float *sx,
                                  const void *U, int r, float *T, void *stream);
 

@@ -156,19 +156,46 @@ __device__ inline uint4 relu8(uint4 x)
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// silu(g) * u in binary64 (g / (1 + exp(-g)) * u), rounded to binary32 and from there to bf16
-__device__ inline float swiglu1(float g, float u)
-{
-    const double gd = (double)g;
-    const double t = gd / (1.0 + exp(-gd)) * (double)u;
-    return (float)t;
-}
+// silu(g) * u = g / (1 + exp(-g)) * u as the binary32 value whose rounding to bf16 (nearest even) equals
+// that of the expression evaluated in binary64 and rounded to binary32 first.
+// Fast path, binary32 throughout: for 2^-30 <= |g| <= 32 and 2^-30 <= |u| <= 2^30 every intermediate
+// is a normal number (exp(-g) in 2^+-47, the quotient above 2^-77, the product in 2^-107 .. 2^35), so
+// the relative error is bounded by that of expf (documented as 1 ulp, taken as 4), of the hardware
+// reciprocal (1 ulp) and three roundings: 13 * 2^-24 in all, at most 13 binary32 ulps of the result.
+// The bf16 rounding of the true value and of the
+// binary64 evaluation (which is within half a binary32 ulp of it after its own rounding) is therefore
+// the one of this value whenever its low 16 bits are more than 32 ulps away from the half-way pattern
+// 0x8000.  Anything else (1 value in 1000, and inputs outside the ranges) is evaluated in binary64.
 __device__ inline uint4 swiglu8(uint4 g, uint4 u)
 {
-    uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w}, o[4];
+    const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w};
+    float gf[8], uf[8], y[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        o[i] = pack_bf16_rne(swiglu1(bf16_lo(gw[i]), bf16_lo(uw[i])), swiglu1(bf16_hi(gw[i]), bf16_hi(uw[i])));
+    for (int i = 0; i < 4; ++i) {
+        gf[2 * i] = bf16_lo(gw[i]); gf[2 * i + 1] = bf16_hi(gw[i]);
+        uf[2 * i] = bf16_lo(uw[i]); uf[2 * i + 1] = bf16_hi(uw[i]);
+    }
+    uint32_t redo = 0;  // the eight fast evaluations are straight-line code; what they leave open is redone below
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float ag = fabsf(gf[i]), au = fabsf(uf[i]);
+        y[i] = gf[i] * __builtin_amdgcn_rcpf(1.0f + expf(-gf[i])) * uf[i];
+        const uint32_t low = __float_as_uint(y[i]) & 0xFFFFu;
+        const bool safe = ag >= 0x1p-30f && ag <= 32.0f && au >= 0x1p-30f && au <= 0x1p30f &&
+                          low - (0x8000u - 32u) > 64u;  // unsigned: |low - 0x8000| > 32
+        redo |= safe ? 0u : 1u << i;
+    }
+    if (redo != 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if ((redo >> i) & 1u) {
+                const double gd = (double)gf[i];
+                y[i] = (float)(gd / (1.0 + exp(-gd)) * (double)uf[i]);
+            }
+    }
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = pack_bf16_rne(y[2 * i], y[2 * i + 1]);
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
@@ -251,6 +278,7 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
                 if (idx < nchunk) {
                     if constexpr (NORM == 4) {
                         v[c] = swiglu8(v[c], orow[idx]);
+                        if (pr.H != nullptr) hrow[idx] = v[c];
                     } else {
                         v[c] = add8(v[c], orow[idx]);
                         hrow[idx] = v[c];
@@ -426,6 +454,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
                 if (idx < nchunk) {
                     if constexpr (NORM == 4) {
                         v[c] = swiglu8(v[c], orow[idx]);
+                        if (pr.H != nullptr) hrow[idx] = v[c];
                     } else {
                         v[c] = add8(v[c], orow[idx]);
                         hrow[idx] = v[c];

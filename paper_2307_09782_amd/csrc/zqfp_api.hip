@@ -73,7 +73,7 @@ const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
 
 extern "C" {
 
-int zqfp_version(void) { return 105; }
+int zqfp_version(void) { return 106; }
 
 const char* zqfp_last_hip_error(void) { return g_last_error.c_str(); }
 
@@ -119,10 +119,11 @@ int zqfp_relu_quantize_act_fp8(const void* X, int64_t M, int64_t K, int64_t ldx,
     return quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{3, nullptr, nullptr, nullptr, 0, nullptr, 0.0f}, stream);
 }
 
-int zqfp_swiglu_quantize_act_fp8(const void* G, const void* Up, int64_t ldu, int64_t M, int64_t K, int64_t ldg,
+int zqfp_swiglu_quantize_act_fp8(const void* G, const void* Up, int64_t ldu, void* H, int64_t M, int64_t K, int64_t ldg,
                                  uint8_t* Xq, float* sx, const void* U, int r, float* T, void* stream)
 {
-    return quantize_common(G, M, K, ldg, Xq, sx, U, r, T, zqfp::Producer{4, nullptr, nullptr, u16(Up), ldu, nullptr, 0.0f}, stream);
+    return quantize_common(G, M, K, ldg, Xq, sx, U, r, T,
+                           zqfp::Producer{4, nullptr, nullptr, u16(Up), ldu, static_cast<uint16_t*>(H), 0.0f}, stream);
 }
 
 size_t zqfp_packed_weight_bytes(int64_t K, int64_t N, int G)

@@ -66,7 +66,7 @@ def lib():
         L.zqfp_relu_quantize_act_fp8.restype = c.c_int
         L.zqfp_relu_quantize_act_fp8.argtypes = [p, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_swiglu_quantize_act_fp8.restype = c.c_int
-        L.zqfp_swiglu_quantize_act_fp8.argtypes = [p, p, i64, i64, i64, i64, p, p, p, c.c_int, p, p]
+        L.zqfp_swiglu_quantize_act_fp8.argtypes = [p, p, i64, p, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_lorc_workspace_bytes.restype = c.c_size_t
         L.zqfp_lorc_workspace_bytes.argtypes = [i64, i64, c.c_int]
         L.zqfp_lorc_factorize.restype = c.c_int
@@ -205,15 +205,18 @@ def relu_quantize_act_fp8(X, U=None):
     return (Xq, sx) if U is None else (Xq, sx, T)
 
 
-def swiglu_quantize_act_fp8(G, Up, U=None):
-    """bf16(silu(G) * Up) fused in front of quantize_act_fp8; same outputs."""
+def swiglu_quantize_act_fp8(G, Up, U=None, H=None):
+    """bf16(silu(G) * Up) fused in front of quantize_act_fp8; same outputs.  H (dense [M, K] bf16, optional)
+    receives the unquantized product."""
     _rows(G, torch.bfloat16), _rows(Up, torch.bfloat16)
     M, K = G.shape
     if tuple(Up.shape) != (M, K):
         raise ZqfpError(-2, "gate / up shapes differ")
+    if H is not None and (tuple(H.shape) != (M, K) or not H.is_contiguous() or H.dtype != torch.bfloat16):
+        raise ZqfpError(-2, "H must be a dense [M, K] bf16 tensor")
     Xq, sx, T, r = _quant_outputs(G, U)
-    _check(lib().zqfp_swiglu_quantize_act_fp8(_ptr(G), _ptr(Up), Up.stride(0), M, K, G.stride(0), _ptr(Xq), _ptr(sx), _ptr(U),
-                                              r, _ptr(T), _stream(G)))
+    _check(lib().zqfp_swiglu_quantize_act_fp8(_ptr(G), _ptr(Up), Up.stride(0), _ptr(H), M, K, G.stride(0), _ptr(Xq), _ptr(sx),
+                                              _ptr(U), r, _ptr(T), _stream(G)))
     return (Xq, sx) if U is None else (Xq, sx, T)
 
 

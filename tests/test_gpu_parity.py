@@ -541,6 +541,42 @@ def test_gated_silu_fused_in_front_of_the_quantizer(K, M, rank):
 
 
 @pytest.mark.gpu
+def test_gated_silu_every_gate_value_bit_exact():
+    """The product silu(g) * u as the kernel rounds it to bf16 (returned through H), for every finite bf16
+    gate value against a spread of up values: ordinary ones, powers of two at the ends of the binary32
+    range, subnormals, values one bf16 step from 1, and random bit patterns.  The kernel evaluates most
+    values in binary32 and only those near a rounding boundary or outside its safe ranges in binary64: all
+    must round as the binary64 evaluation does."""
+    K = 8192
+    gates = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    gates[(gates & 0x7F80) == 0x7F80] = 0x3F80          # infinities and NaNs: 1.0 instead
+    gates = gates.reshape(8, K)
+    fixed = np.array([1.0, -1.0, 0.5, -0.5, 3.140625, -2.71875, 1.0078125, 0.99609375, 1e-3, -1e3, 2.0 ** -30, 2.0 ** -31,
+                      2.0 ** 30, 2.0 ** 31, 2.0 ** -126, 2.0 ** -130, -2.0 ** -133, 2.0 ** 100, -2.0 ** 127, 2.0 ** -60,
+                      0.0, -0.0, 6.0, 448.0], dtype=np.float32)
+    ups = list(inputs.f32_to_bf16_bits(fixed))
+    rng = np.random.default_rng(77)
+    G_rows, U_rows = [], []
+    for u in ups:
+        for b in range(8):
+            G_rows.append(gates[b]); U_rows.append(np.full(K, u, np.uint16))
+    for j in range(24):                                   # random up values against every gate value
+        r = rng.integers(0, 65536, size=(8, K), dtype=np.uint32).astype(np.uint16)
+        r[(r & 0x7F80) == 0x7F80] ^= 0x4000
+        if j >= 12:                                       # half of them of ordinary magnitude (exponent field 112 .. 135)
+            r = (r & 0x807F) | (rng.integers(112, 136, size=(8, K), dtype=np.uint32).astype(np.uint16) << 7)
+        for b in range(8):
+            G_rows.append(gates[b]); U_rows.append(r[b])
+    G = np.ascontiguousarray(np.stack(G_rows)); Up = np.ascontiguousarray(np.stack(U_rows))
+    H = torch.empty(G.shape, dtype=torch.bfloat16, device="cuda")
+    zqfp.swiglu_quantize_act_fp8(bf16_tensor(G), bf16_tensor(Up), H=H)
+    got = _sync_np(H.view(torch.int16)).view(np.uint16)
+    want = oracle.swiglu_bf16(G, Up)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, (len(bad), [(hex(G[i, j]), hex(Up[i, j]), hex(got[i, j]), hex(want[i, j])) for i, j in bad[:8]])
+
+
+@pytest.mark.gpu
 def test_fused_producer_argument_checks():
     X = bf16_tensor(inputs.make_x(CFG["tiny"], 4))
     g = bf16_tensor(_gain_bits(256).reshape(1, -1)).reshape(-1).contiguous()
@@ -551,7 +587,7 @@ def test_fused_producer_argument_checks():
     with pytest.raises(zqfp.ZqfpError):
         zqfp.swiglu_quantize_act_fp8(X, X[:, :128])
     lib = zqfp.lib()
-    assert lib.zqfp_swiglu_quantize_act_fp8(X.data_ptr(), None, 256, 4, 256, 256, None, None, None, 0, None, None) != 0
+    assert lib.zqfp_swiglu_quantize_act_fp8(X.data_ptr(), None, 256, None, 4, 256, 256, None, None, None, 0, None, None) != 0
     assert lib.zqfp_relu_quantize_act_fp8(X.data_ptr(), 4, 65536, 65536, X.data_ptr(), X.data_ptr(), None, 0, None, None) != 0
 
 
