@@ -311,7 +311,8 @@ def gptq_fp4(W, Hinv_u, G, mode):
         q_k = S * e2m1(w_k / S);   err = (w_k - q_k) / Hinv_u[k, k];   w_j -= Hinv_u[k, j] * err  for j > k.
     A group's scale is fixed when its first channel is reached, from the weights as they stand then
     (M1: S = 2^n, least n with amax <= 6 * 2^n; M2: S = c * 2^-k with c = column absmax of the ORIGINAL W / 6,
-    least k >= 0 with amax_max <= amax * 2^k, at most 15).
+    least k >= 0 with amax_max <= amax * 2^k, at most 15).  The value that is encoded is w / S; under M2 it is
+    formed as the plain packer forms it, fl32(fl32(w) / c) * 2^k: one binary32 division, then an exact shift.
     Returns codes [K,N] u8, exps [K/G,N] u8, c [N] f32 and the final de-quantized weight [K,N] f64."""
     _chk(W, np.uint16, 2)
     K, N = W.shape
@@ -344,7 +345,13 @@ def gptq_fp4(W, Hinv_u, G, mode):
                     kg[nz & (colmax <= amax * 2.0 ** t)] = t
                 exps[k // G] = (127 - kg).astype(np.uint8)
                 S = c.astype(np.float64) * np.exp2(-kg.astype(np.float64))
-        codes[k] = e2m1_encode_array(Wf[k] / S)
+        if mode == 1:
+            y = Wf[k] / S                                   # a power of two: exact
+        else:
+            # the plain packer's rule (orc_pack_weight): the working weight rounded to binary32, ONE binary32
+            # division by the column scale, then the exact shift by 2^k -- so that H = I gives the packer's codes
+            y = (Wf[k].astype(np.float32) / c).astype(np.float64) * np.exp2(kg.astype(np.float64))
+        codes[k] = e2m1_encode_array(y)
         Q[k] = np.where(codes[k] & 8, -1.0, 1.0) * _E2M1_GRID[codes[k] & 7] * S
         err = (Wf[k] - Q[k]) / Hinv_u[k, k]
         if k + 1 < K:

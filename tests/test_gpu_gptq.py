@@ -53,6 +53,13 @@ def test_identity_hessian_gives_the_plain_packers_blob_bit_for_bit(K, N, G, mode
     assert np.array_equal(g[off_cs:off_cs + 4 * Np], w[off_cs:off_cs + 4 * Np])
     for a, b in zip(_unpacked(got, K, N, G), _unpacked(want, K, N, G)):
         assert np.array_equal(a, b)
+    # and against the oracle itself: its plain packer, and its GPTQ under the same identity Hessian
+    codes_o, exps_o, c_o, _ = oracle.pack_weight(W, G, mode)
+    for a, b in zip(_unpacked(got, K, N, G), (codes_o, exps_o, c_o)):
+        assert np.array_equal(a, b)
+    codes_g, exps_g, c_g, _ = oracle.gptq_fp4(W, np.eye(K), G, mode)
+    for a, b in zip(_unpacked(got, K, N, G), (codes_g, exps_g, c_g)):
+        assert np.array_equal(a, b)
 
 
 @pytest.mark.parametrize("K,N,G,mode", [(256, 64, 128, 1), (512, 200, 64, 2), (512, 96, 256, 1), (1024, 130, 128, 2)])

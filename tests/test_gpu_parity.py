@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from paper_2307_09782_amd import inputs, zqfp
-from _util import bf16_tensor, bits_equal_f32, check_gemm, f16_tensor, f32_tensor, u8_tensor
+from _util import ELEM, bf16_tensor, bits_equal_f32, check_gemm, f16_tensor, f32_tensor, u8_tensor
 
 pytestmark = pytest.mark.gpu
 
@@ -225,12 +225,47 @@ def test_gemm_small_shapes_full_compare(M, K, N, G, mode, r):
     check_gemm(Y, Y_o, Sabs, f"M{M} K{K} N{N} G{G} mode{mode} r{r}")
 
 
-def test_gemm_bf16_output():
-    Y, Y_o, Sabs = _gemm_case(40, 512, 96, 128, 1, 0, out_dtype=torch.bfloat16)
-    want = torch.from_numpy(Y_o).to(torch.bfloat16).float().numpy()
-    # the bf16 rounding of a value within tolerance of the oracle's: equal or one bf16 ulp apart
-    assert np.all(np.abs(Y - want) <= np.abs(want) * 2.0 ** -7 + 1e-30)
-    assert (Y == want).mean() > 0.99
+def _check_bf16(Y, Y_o, Sabs, what):
+    """bfloat16 output against the oracle's float32 result: the stored value is the bfloat16 rounding of a
+    float32 value within the GEMM tolerance of the oracle's, so it is the oracle's own rounding or the bfloat16
+    neighbour of it (where the two float32 values straddle a rounding boundary), and never further from the
+    oracle than the tolerance plus half a bfloat16 step."""
+    want = torch.from_numpy(np.asarray(Y_o, np.float32)).to(torch.bfloat16).float().numpy().astype(np.float64)
+    Y = np.asarray(Y, np.float64)
+    assert np.all(np.abs(Y - Y_o) <= ELEM * Sabs + np.abs(Y_o) * 2.0 ** -8 + 1e-300), what
+    assert np.all(np.abs(Y - want) <= np.abs(want) * 2.0 ** -7 + 1e-300), what
+    assert (Y == want).mean() > 0.99, what
+
+
+@pytest.mark.parametrize("M,K,N,G,mode,r", [
+    (40, 512, 96, 128, 1, 0),       # 64 x 128 tile
+    (16, 1024, 272, 128, 1, 8),     # decode form, LoRC in registers, ragged N
+    (5, 512, 1664, 128, 2, 0),      # decode form, strips in pairs, column scales
+    (7, 512, 48, 128, 2, 16),       # decode form, LoRC read in place
+    (16, 8192, 80, 128, 1, 8),      # decode form, upper band in LDS
+    (20, 8320, 48, 128, 1, 0),      # streaming fallback
+    (16, 11008, 96, 128, 1, 8),     # streaming fallback for at most 16 tokens, LoRC
+    (64, 4096, 128, 128, 1, 8),     # K split through the workspace: the reduce kernel stores
+    (100, 3072, 136, 128, 2, 3),    # K split 3 ways, ragged M and N
+    (64, 1024, 272, 128, 1, 8),     # 64 x 128 tiles, two wave groups
+    (200, 1280, 400, 256, 2, 0),    # 64 x 128 tiles, several each way
+])
+def test_gemm_bf16_output_small_shapes(M, K, N, G, mode, r):
+    Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r, out_dtype=torch.bfloat16)
+    _check_bf16(Y, Y_o, Sabs, f"bf16 M{M} K{K} N{N} G{G} mode{mode} r{r}")
+
+
+@pytest.mark.parametrize("name,M", [("llama7b_qkv", 4096), ("opt1p3b_fc1", 2048), ("llama7b_qkv", 1000),
+                                    ("llama7b_qkv", 512), ("llama7b_qkv", 256), ("llama13b_ffn_lorc", 2048),
+                                    ("llama70b_ffn_decode", 64), ("llama70b_ffn_decode", 16),
+                                    ("llama70b_ffn_down", 16), ("llama7b_ffn_down", 64)])
+def test_gemm_bf16_output_full_size_sampled(name, M):
+    """Every tile shape the planner picks for the benchmark configurations (128 x 256, 256 x 256, 128 x 192,
+    128 x 128 or 64 x 128, with and without a K-split), the decode form and its chunked-K variant, storing bfloat16."""
+    cfg = CFG[name]
+    Y, Y_o, Sabs = _gemm_case(M, cfg.K, cfg.N, cfg.G, cfg.mode, cfg.rank, seed_cfg=name, full=False,
+                              out_dtype=torch.bfloat16)
+    _check_bf16(Y, Y_o, Sabs, f"bf16 {name} M={M}")
 
 
 def test_gemm_zero_rows_and_signed_zeros():

@@ -37,11 +37,19 @@ def test_identity_hessian_reduces_to_the_plain_packer():
         codes, exps, c, Q = oracle.gptq_fp4(W, np.eye(cfg.K), G, mode)
         codes_p, exps_p, c_p, _ = oracle.pack_weight(W, G, mode)
         assert np.array_equal(exps, exps_p) and np.array_equal(c, c_p)
-        if mode == 1:
-            assert np.array_equal(codes, codes_p)
-        else:  # the packer divides by c in binary32 before the shift; away from ties the codes are the same
-            assert np.mean(codes != codes_p) < 1e-3
+        assert np.array_equal(codes, codes_p)  # both modes: M2 divides by c in binary32 on either side
         assert np.allclose(Q, oracle.dequant_weight(codes, exps, c, G), rtol=0, atol=0)
+
+
+def test_identity_hessian_reduces_to_the_plain_packer_on_a_larger_matrix():
+    """Half a million weights under M2, where a binary64 division in place of the packer's binary32 one would
+    move a few hundred codes that sit next to a rounding boundary."""
+    cfg = inputs.Config("g", 1024, 512, (1,), 128, 2, 0.0, 4, 20.0, 0, 7)
+    W = inputs.make_w(cfg)
+    for G, mode in ((128, 2), (256, 2), (128, 1)):
+        codes, exps, c, _ = oracle.gptq_fp4(W, np.eye(cfg.K), G, mode)
+        codes_p, exps_p, c_p, _ = oracle.pack_weight(W, G, mode)
+        assert np.array_equal(codes, codes_p) and np.array_equal(exps, exps_p) and np.array_equal(c, c_p)
 
 
 def test_two_channels_worked_by_hand():

@@ -133,3 +133,68 @@ def test_layernorm_power_of_two_scaling_cancels_when_eps_is_negligible():
     g, b = _gain(cfg.K), _bias(cfg.K)
     Y0 = oracle.layernorm_bf16(X, g, b, 1e-30)
     assert np.array_equal(oracle.layernorm_bf16(_bf16(_f32(X) * 8.0), g, b, 1e-30), Y0)
+
+
+# ------------------------------------------------------------------ the fixed binary32 operation order
+# The codes that follow a normalisation have one right answer only because its arithmetic is a fixed sequence
+# of IEEE operations.  These pins retrace that sequence with another library's binary32 operations (PyTorch CPU
+# tensors: every torch op below rounds once to binary32) and ask for the same bits; each also shows that the
+# neighbouring order of operations does NOT give the same bits, so a swap inside the oracle would fail here.
+def _t32(bits):
+    return torch.from_numpy(_f32(bits).copy())
+
+
+def _seq_sum64(v):
+    """Left-to-right binary64 sum of every row (numpy's cumulative sum adds in index order)."""
+    return np.cumsum(v, axis=1)[:, -1]
+
+
+def _bf16_bits_of(t):
+    return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+# The two orders differ in the last binary32 bit for about half the elements, which moves the bfloat16 result of
+# about one element in 2^17: the large case (2M elements) is there so that the other order is seen to differ.
+@pytest.mark.parametrize("name,M", [("tiny", 16), ("llama7b_qkv", 512), ("llama13b_ffn_lorc", 5), ("llama70b_ffn_decode", 4)])
+def test_rmsnorm_operation_order_retraced_in_binary32(name, M):
+    cfg = CFG[name]
+    X = inputs.make_x(cfg, M)
+    g = _gain(cfg.K)
+    eps = 1e-5
+    x64 = _f32(X).astype(np.float64)
+    ss = _seq_sum64(x64 * x64)                                        # squares of bf16 values are exact in binary64
+    ms = torch.from_numpy((ss / float(cfg.K)).astype(np.float32))     # ms = fl32(ss / K)
+    rstd = 1.0 / torch.sqrt(ms + torch.tensor(eps, dtype=torch.float32))
+    assert rstd.dtype == torch.float32
+    x, gg = _t32(X), _t32(g)
+    want = _bf16_bits_of((x * rstd[:, None]) * gg[None, :])           # (x * rstd) * g
+    got = oracle.rmsnorm_bf16(X, g, eps)
+    assert np.array_equal(got, want)
+    other = _bf16_bits_of(x * (rstd[:, None] * gg[None, :]))          # x * (rstd * g): another rounding
+    if cfg.K * M >= 1 << 21:
+        assert not np.array_equal(other, want)
+
+
+@pytest.mark.parametrize("name,M", [("tiny", 16), ("opt1p3b_fc1", 9), ("llama7b_qkv", 512), ("llama70b_ffn_decode", 4)])
+def test_layernorm_operation_order_retraced_in_binary32(name, M):
+    cfg = CFG[name]
+    X = _bf16(_f32(inputs.make_x(cfg, M)) + 0.75)
+    g, b = _gain(cfg.K), _bias(cfg.K)
+    eps = 1e-5
+    x64 = _f32(X).astype(np.float64)
+    s1, s2 = _seq_sum64(x64), _seq_sum64(x64 * x64)
+    mean = s1 / float(cfg.K)
+    var = np.maximum(s2 / float(cfg.K) - mean * mean, 0.0)
+    mu = torch.from_numpy(mean.astype(np.float32))
+    v = torch.from_numpy(var.astype(np.float32))
+    rstd = 1.0 / torch.sqrt(v + torch.tensor(eps, dtype=torch.float32))
+    x, gg, bb = _t32(X), _t32(g), _t32(b)
+    d = x - mu[:, None]
+    want = _bf16_bits_of(((d * rstd[:, None]) * gg[None, :]) + bb[None, :])
+    got = oracle.layernorm_bf16(X, g, b, eps)
+    assert np.array_equal(got, want)
+    other = _bf16_bits_of((d * (rstd[:, None] * gg[None, :])) + bb[None, :])
+    fused = _bf16_bits_of(torch.addcmul(bb[None, :].expand_as(d).to(torch.float64), (d * rstd[:, None]).to(torch.float64),
+                                        gg[None, :].to(torch.float64).expand_as(d)).to(torch.float32))  # one rounding for a*g+b
+    if cfg.K * M >= 1 << 21:
+        assert not np.array_equal(other, want) and not np.array_equal(fused, want)
