@@ -27,8 +27,13 @@
  *   - Shape limits: K % 128 == 0, G % 32 == 0, K % G == 0, K / G <= 256,
  *     0 <= r <= 64 (else ZQFP_E_SHAPE).
  *     M and N are arbitrary (M == 0 or N == 0 is a successful no-op).
- *     Pointers must be 16-byte aligned and ldx, ldw multiples of 8 elements
- *     (ZQFP_E_ALIGN).
+ *     X, Xq, U, Y, Omega, gain / bias / residual pointers and workspaces must be
+ *     16-byte aligned, packed blobs 256-byte aligned, and ldx (and the other
+ *     activation row strides) multiples of 8 elements (ZQFP_E_ALIGN).  The
+ *     offline weight-side calls read W element by element: W needs only its
+ *     natural 2-byte alignment and ldw >= N.
+ *   - Thread safety: calls may be made from several host threads; the error
+ *     text is per thread, one-time kernel set-up is serialised inside.
  */
 #ifndef ZQFP_H
 #define ZQFP_H
@@ -46,6 +51,9 @@ extern "C" {
 #define ZQFP_E_ALIGN (-3) /* pointer or leading dimension alignment */
 #define ZQFP_E_MODE (-4)  /* unknown scale mode / output dtype / accumulation mode */
 #define ZQFP_E_HIP (-5)   /* a HIP call failed; see zqfp_last_hip_error() */
+#define ZQFP_E_WORKSPACE (-6) /* workspace given but smaller than the query says,
+                                 or (static variant) larger than the built-in array */
+#define ZQFP_E_BLOB (-7)  /* zqfp_packed_weight_check: not a blob of this (K, N, G) */
 
 #define ZQFP_SCALE_M1 1 /* S^ = 2^ceil(log2 S) per group               */
 #define ZQFP_SCALE_M2 2 /* S^_g = S_max / 2^ceil(log2(S_max / S_g))    */
@@ -228,6 +236,22 @@ int zqfp_pack_weight_fp4(const void *W, int64_t K, int64_t N, int64_t ldw,
                          int G, int mode, void *packed, void *stream);
 
 /*
+ * packed_weight_check -- does a blob belong to (K, N, G)?  The GEMM calls take
+ * K, N and G as arguments because the blob's header lives in device memory
+ * and reading it there would force a synchronization; a blob packed for other
+ * sizes would be read with the wrong layout.  A caller that wants the check
+ * copies the blob's first ZQFP_BLOB_HEADER_BYTES bytes to the host once (after
+ * packing has finished) and passes them here.  Pure host logic, no GPU call.
+ *
+ *   header  HOST pointer to the first ZQFP_BLOB_HEADER_BYTES bytes of a blob
+ * Returns ZQFP_OK; ZQFP_E_NULL; ZQFP_E_SHAPE if (K, N, G) itself is outside the
+ * limits; ZQFP_E_BLOB if the magic number, the layout version, K, N, G or the
+ * section offsets are not those of a blob of (K, N, G).
+ */
+#define ZQFP_BLOB_HEADER_BYTES 256
+int zqfp_packed_weight_check(const void *header, int64_t K, int64_t N, int G);
+
+/*
  * lorc_factorize -- the two low-rank matrices of LoRC (paper Section 3: singular
  * value decomposition of the error matrix E = W - W^, the original weight minus
  * the quantized one; Appendix A: rank 8 for LLaMA, 16..56 for OPT).  Offline
@@ -316,12 +340,15 @@ int zqfp_unpack_codes(const void *packed, int64_t K, int64_t N, int G,
  *            K (K is then cut into slices whose float32 partial tiles are summed
  *            in fixed order by a second kernel).  NULL is always accepted: the
  *            call then runs without the split (same result within tolerance).
+ *   workspace_bytes  size of what `workspace` points to.  A non-NULL workspace
+ *            smaller than the query's answer is refused (ZQFP_E_WORKSPACE) and
+ *            nothing is enqueued.
  */
 size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int zqfp_w4a8_gemm(const uint8_t *Xq, const float *sx, int64_t M, int64_t K,
                    const void *packed, int64_t N, int G,
                    void *Y, int64_t ldy, int out_dtype, int accum,
-                   void *workspace, void *stream);
+                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * w4a8_gemm_lorc -- the same layer with the LoRC correction fused into the
@@ -336,30 +363,7 @@ int zqfp_w4a8_gemm_lorc(const uint8_t *Xq, const float *sx, int64_t M, int64_t K
                         const void *packed, int64_t N, int G,
                         const float *T, const void *V, int r,
                         void *Y, int64_t ldy, int out_dtype, int accum,
-                        void *workspace, void *stream);
-
-/*
- * Measurement probes (no part of the paper's method): what the device itself
- * sustains, for reporting roofline fractions against measured ceilings next to
- * the published peaks.  Both only enqueue work on `stream`; the caller times it.
- *
- * zqfp_probe_stream_read -- a plain streaming read of `bytes` bytes at `src`
- *   (device, 16-byte aligned; the last bytes % (workgroups * 32 KB) are not
- *   read).  sink: device, >= 4 * workgroups bytes, written at most once per
- *   workgroup with a value that means nothing.
- * zqfp_probe_mfma -- `iters` rounds of 32 independent
- *   v_mfma_scale_f32_16x16x128_f8f6f4 instructions (FP8 x FP4) per wave, 8 waves
- *   per workgroup, operands held in registers: 2 * 16*16*128 * 32 * 8 * iters *
- *   workgroups floating-point operations in total.  operands: device, 4096
- *   bytes of anything; sink: device, >= 2048 * workgroups bytes.
- *
- * Return ZQFP_OK, ZQFP_E_NULL, ZQFP_E_SHAPE (non-positive sizes), ZQFP_E_ALIGN
- * or ZQFP_E_HIP.
- */
-int zqfp_probe_stream_read(const void *src, int64_t bytes, void *sink,
-                           int workgroups, void *stream);
-int zqfp_probe_mfma(const void *operands, void *sink, int iters,
-                    int workgroups, void *stream);
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

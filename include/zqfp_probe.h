@@ -1,0 +1,42 @@
+/*
+ * zqfp_probe.h -- measurement probes exported by libzqfp next to its C ABI
+ * (zqfp.h).  They are tooling for the benchmark, no part of the W4A8 path: two
+ * kernels that show what the device itself sustains, so that roofline
+ * fractions can be quoted against measured ceilings as well as published peaks.
+ */
+#ifndef ZQFP_PROBE_H
+#define ZQFP_PROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Both only enqueue work on `stream` (a hipStream_t as void*); the caller times it.
+ * Error codes are those of zqfp.h.
+ *
+ * zqfp_probe_stream_read -- a plain streaming read of `bytes` bytes at `src`
+ *   (device, 16-byte aligned; the last bytes % (workgroups * 32 KB) are not
+ *   read).  sink: device, >= 4 * workgroups bytes, written at most once per
+ *   workgroup with a value that means nothing.
+ * zqfp_probe_mfma -- `iters` rounds of 32 independent
+ *   v_mfma_scale_f32_16x16x128_f8f6f4 instructions (FP8 x FP4) per wave, 8 waves
+ *   per workgroup, operands held in registers: 2 * 16*16*128 * 32 * 8 * iters *
+ *   workgroups floating-point operations in total.  operands: device, 4096
+ *   bytes of anything; sink: device, >= 2048 * workgroups bytes.
+ *
+ * Return ZQFP_OK, ZQFP_E_NULL, ZQFP_E_SHAPE (non-positive sizes), ZQFP_E_ALIGN
+ * or ZQFP_E_HIP.
+ */
+int zqfp_probe_stream_read(const void *src, int64_t bytes, void *sink,
+                           int workgroups, void *stream);
+int zqfp_probe_mfma(const void *operands, void *sink, int iters,
+                    int workgroups, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZQFP_PROBE_H */

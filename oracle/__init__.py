@@ -34,15 +34,29 @@ def build_oracle():
     return _LIB
 
 
+def build_oracle_sanitized(out, cc="/opt/rocm/llvm/bin/clang"):
+    """The same source under AddressSanitizer + UndefinedBehaviorSanitizer, for the test that re-runs the pins on
+    it (clang, so that one sanitizer runtime serves this library and the sanitized host build of the HIP library;
+    single-threaded: the OpenMP pragmas are ignored).  The process that loads it needs the runtime preloaded."""
+    flags = [f for f in CFLAGS if f not in ("-fopenmp", "-O2")]
+    subprocess.check_call([cc, "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-Wno-unknown-pragmas", "-Wno-source-uses-openmp", *flags,
+                           "-o", out, _SRC, "-lm"])
+    return out
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-            build_oracle()
-        L = ctypes.CDLL(_LIB)
+        path = os.environ.get("ZQFP_ORACLE_LIB")  # another build of this same source (the sanitizer run sets it)
+        if not path:
+            if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+                build_oracle()
+            path = _LIB
+        L = ctypes.CDLL(path)
         c = ctypes
         p = c.c_void_p
         L.orc_e4m3_decode.restype = c.c_double

@@ -75,5 +75,32 @@ def build_lib(verbose=False, jobs=8):
     return LIB
 
 
+def sanitizer_runtime():
+    """Path of the AddressSanitizer runtime of the compiler that hipcc drives (to be preloaded by a process
+    that loads a library built by build_host_sanitized)."""
+    clang = os.path.join(os.path.dirname(os.path.realpath(HIPCC)), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    return _run([clang, "--print-file-name=libclang_rt.asan-x86_64.so"]).strip()
+
+
+def build_host_sanitized(out):
+    """libzqfp with the HOST side of the C ABI (csrc/zqfp_api.hip: argument checks, dispatch, the header check)
+    compiled under AddressSanitizer + UndefinedBehaviorSanitizer; device code and the kernels' launchers are the
+    ordinary objects of the last build_lib().  For CPU-side tests only."""
+    objs = [os.path.join(OBJDIR, os.path.basename(s)[:-4] + ".o") for s in sources()]
+    if not all(os.path.exists(o) for o in objs):
+        build_lib()
+    api = os.path.join(CSRC, "zqfp_api.hip")
+    api_o = os.path.join(os.path.dirname(out), "zqfp_api.san.o")
+    flags = [f for f in FLAGS if f != "-O3"]
+    _run([HIPCC, *flags, "-O1", "-g", "-fno-omit-frame-pointer", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+          "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined", "-c", api, "-o", api_o])
+    others = [o for o in objs if os.path.basename(o) != "zqfp_api.o"]
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+          "-o", out, api_o, *others])
+    return out
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))

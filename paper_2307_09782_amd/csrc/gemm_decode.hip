@@ -11,6 +11,8 @@
 // 1 KB fragment per matrix instruction plus its exponent dword.  The fragments
 // of the next strip are in flight while the current strip is multiplied,
 // reduced across the waves in LDS (fixed order, no atomics) and stored.
+#include <atomic>
+
 #include "zqfp_internal.h"
 
 namespace zqfp {
@@ -235,16 +237,15 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
     // default limit of dynamic LDS, which is a per-function setting)
     const size_t smem = (exact && KPW >= 8) ? (size_t)NW * KPW * 2048 : 0;
     if (smem > 0) {
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        static OnceStatus raised;
+        if (hipError_t e = run_once(raised, [&] {
+                hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, false>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+                if (e1 != hipSuccess) return e1;
+                return hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            }); e != hipSuccess)
+            return e;
     }
 #define ZQ_LAUNCH(EX, LR) \
     hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial)
@@ -256,10 +257,26 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
 
 }  // namespace
 
+// compute units of the (single) device, asked once
+int compute_units()
+{
+    static std::atomic<int> cus{0};
+    int n = cus.load(std::memory_order_relaxed);
+    if (n == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus.store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace)
 {
     if (M < 1 || M > 16) return false;
     if (L.nkt <= 64) return true;
+    if (plan_decode(L.nkt).chunks > compute_units()) return false;  // every chunk needs a workgroup of its own
     // longer K: in chunks through the workspace, if there are strips enough to give every workgroup
     // several (below that the streaming kernel, one launch and no prologue per chunk, is faster)
     return workspace != nullptr && L.nstrips * plan_decode(L.nkt).chunks >= 1024;
@@ -269,14 +286,7 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
                               Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s)
 {
     if (L.N == 0) return hipSuccess;
-    static int cus = 0;  // compute units of the (single) device, asked once
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
-    }
+    const int cus = compute_units();
     const bool exact = accum == 0;
     const int m = (int)M;
     const DecodePlan plan = plan_decode(L.nkt);

@@ -595,13 +595,11 @@ hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8
     const int per = (units + 7) / 8;
     const size_t smem = C::NSTAGE * C::STAGE;
     auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, EXACT>;
-    static bool attr_done = false;  // raising the dynamic LDS limit is a per-function, per-process setting
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static OnceStatus attr;  // raising the dynamic LDS limit is a per-function, per-process setting (one flag per instantiation)
+    if (hipError_t e = run_once(attr, [&] {
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        }); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(C::THREADS), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy,
                        out_dtype, tiles_m, tiles_n, ksplit, kslice, partial);
     hipError_t e = hipGetLastError();

@@ -161,13 +161,12 @@ hipError_t launch_gptq_pack(const uint16_t* W, int64_t ldw, const BlobLayout& L,
     float* colmax = reinterpret_cast<float*>(take((size_t)N * 4));
     hipLaunchKernelGGL(k_gptq_init, dim3((unsigned)((L.Np + 255) / 256)), dim3(256), 0, s, W, ldw, L, mode, Wf, colmax, blob);
     const size_t lds = (size_t)B * 64 * 4;
-    static bool attr_done = false;  // 256-row blocks need more than the default dynamic-LDS limit
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gptq_block), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           256 * 64 * 4);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static OnceStatus attr;  // 256-row blocks need more than the default dynamic-LDS limit
+    if (hipError_t e = run_once(attr, [&] {
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(k_gptq_block), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       256 * 64 * 4);
+        }); e != hipSuccess)
+        return e;
     for (int64_t i0 = 0; i0 < K; i0 += B) {
         hipLaunchKernelGGL(k_gptq_block, dim3((unsigned)((N + 63) / 64)), dim3(64), lds, s, Wf, U, L, mode, B, i0, colmax, Err, blob);
         const int64_t behind = K - (i0 + B);

@@ -1,7 +1,9 @@
 // C ABI of libzqfp (declared in include/zqfp.h): argument checks and kernel
 // dispatch.  No call here synchronizes, allocates or frees device memory.
 #include "../../include/zqfp.h"
+#include "../../include/zqfp_probe.h"
 
+#include <cstring>
 #include <string>
 
 #include "zqfp_internal.h"
@@ -18,9 +20,23 @@ int hip_fail(hipError_t e)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// bytes of float32 partial results the GEMM of (M, K, N) hands through a workspace (0: none)
+size_t gemm_workspace_need(int64_t M, int64_t K, int64_t N)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
+    const int64_t Np = (N + 15) / 16 * 16;
+    if (M <= 16) {  // decode form: K beyond 64 k-tiles is served in chunks
+        const zqfp::DecodePlan d = zqfp::plan_decode(K / 128);
+        return d.chunks > 1 ? (size_t)d.chunks * (size_t)M * (size_t)Np * sizeof(float) : 0;
+    }
+    if (N < 64) return 0;
+    const zqfp::TilePlan p = zqfp::plan_tiles(M, Np, K / 128);
+    return p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)Np * sizeof(float) : 0;
+}
+
 int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
                 const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace,
-                void* stream)
+                size_t workspace_bytes, void* stream)
 {
     if (M < 0 || N < 0 || r < 0 || r > 64) return ZQFP_E_SHAPE;
     zqfp::BlobLayout L;
@@ -31,6 +47,10 @@ int gemm_common(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const 
     if (!Xq || !sx || !packed || !Y) return ZQFP_E_NULL;
     if (r > 0 && (!T || !V)) return ZQFP_E_NULL;
     if (ldy < N) return ZQFP_E_SHAPE;
+    if (workspace != nullptr && workspace_bytes < gemm_workspace_need(M, K, N)) {
+        g_last_error = "workspace smaller than zqfp_gemm_workspace_bytes(M, K, N)";
+        return ZQFP_E_WORKSPACE;
+    }
     if (!aligned16(Xq) || !aligned16(Y) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0)
         return ZQFP_E_ALIGN;
     zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
@@ -145,6 +165,21 @@ int zqfp_pack_weight_fp4(const void* W, int64_t K, int64_t N, int64_t ldw, int G
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
+int zqfp_packed_weight_check(const void* header, int64_t K, int64_t N, int G)
+{
+    static_assert(sizeof(zqfp::BlobHeader) <= ZQFP_BLOB_HEADER_BYTES, "header size");
+    if (!header) return ZQFP_E_NULL;
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L)) return ZQFP_E_SHAPE;
+    zqfp::BlobHeader h;
+    std::memcpy(&h, header, sizeof h);
+    const bool ok = h.magic == zqfp::kBlobMagic && h.version == zqfp::kBlobVersion && h.K == L.K && h.N == L.N &&
+                    h.Np == L.Np && h.G == L.G && h.Gs == L.Gs && h.ngs == L.ngs && h.ngq == L.ngq &&
+                    (h.mode == ZQFP_SCALE_M1 || h.mode == ZQFP_SCALE_M2) && h.off_codes == L.off_codes &&
+                    h.off_exps == L.off_exps && h.off_colscale == L.off_colscale && h.total == L.total;
+    return ok ? ZQFP_OK : ZQFP_E_BLOB;
+}
+
 int zqfp_unpack_codes(const void* packed, int64_t K, int64_t N, int G, uint8_t* codes, uint8_t* exps, float* colscale,
                       void* stream)
 {
@@ -157,31 +192,20 @@ int zqfp_unpack_codes(const void* packed, int64_t K, int64_t N, int G, uint8_t* 
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
-size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N)
-{
-    // only the tiled form with a K-split uses one: float32 partial tiles, one set per slice of K
-    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
-    const int64_t Np = (N + 15) / 16 * 16;
-    if (M <= 16) {  // decode form: K beyond 64 k-tiles is served in chunks
-        const zqfp::DecodePlan d = zqfp::plan_decode(K / 128);
-        return d.chunks > 1 ? (size_t)d.chunks * (size_t)M * (size_t)Np * sizeof(float) : 0;
-    }
-    if (N < 64) return 0;
-    const zqfp::TilePlan p = zqfp::plan_tiles(M, Np, K / 128);
-    return p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)Np * sizeof(float) : 0;
-}
+size_t zqfp_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N) { return gemm_workspace_need(M, K, N); }
 
 int zqfp_w4a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
-                   void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, void* stream)
+                   void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return gemm_common(Xq, sx, M, K, packed, N, G, nullptr, nullptr, 0, Y, ldy, out_dtype, accum, workspace, stream);
+    return gemm_common(Xq, sx, M, K, packed, N, G, nullptr, nullptr, 0, Y, ldy, out_dtype, accum, workspace, workspace_bytes,
+                       stream);
 }
 
 int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
                         const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum,
-                        void* workspace, void* stream)
+                        void* workspace, size_t workspace_bytes, void* stream)
 {
-    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, stream);
+    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, workspace_bytes, stream);
 }
 
 size_t zqfp_lorc_workspace_bytes(int64_t K, int64_t N, int r)

@@ -5,7 +5,22 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace zqfp {
+
+// One-time set-up that several host threads may reach together (raising a kernel's dynamic-LDS limit is a
+// per-function setting): the first caller runs `f`, the others wait for it and all see its status.
+struct OnceStatus {
+    std::once_flag flag;
+    hipError_t err = hipSuccess;
+};
+template <class F>
+inline hipError_t run_once(OnceStatus& o, F&& f)
+{
+    std::call_once(o.flag, [&] { o.err = f(); });
+    return o.err;
+}
 
 // ---------------------------------------------------------------------------
 // Packed weight blob
@@ -56,6 +71,7 @@ inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
 {
     if (K <= 0 || N < 0 || G <= 0 || K % 128 != 0 || G % 32 != 0 || K % G != 0) return false;
     if (K / G > 256) return false;
+    if (K / 128 >= 4096) return false;  // the k-tile -> group division by multiplication (gq_magic) is exact below this
     L->K = K; L->N = N; L->Np = (N + 15) / 16 * 16;
     L->nstrips = L->Np / 16; L->nkt = K / 128;
     L->G = G; L->Gs = (G % 128 == 0) ? G : gcd_int(G, 128);
@@ -251,6 +267,7 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                               int accum, void* workspace, hipStream_t s);
 bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace);
+int compute_units();  // of the current device (asked once)
 // Y[m,n] = (sx[m] c[n]) * sum_s partial[s][m][n] (+ T.V): the second kernel of every K-split
 hipError_t launch_splitk_reduce(const float* partial, int slices, int64_t M, const uint8_t* blob, const BlobLayout& L,
                                 const float* sx, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s);

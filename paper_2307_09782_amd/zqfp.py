@@ -12,13 +12,16 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libzqfp.so")
+# ZQFP_LIB_PATH names another build of the same library (e.g. one whose host code is compiled with sanitizers)
+LIB_PATH = os.environ.get("ZQFP_LIB_PATH") or os.path.join(_HERE, "libzqfp.so")
 
 SCALE_M1, SCALE_M2 = 1, 2
 OUT_F32, OUT_BF16 = 0, 1
 ACCUM_EXACT, ACCUM_FAST = 0, 1
 
-_ERR = {-1: "ZQFP_E_NULL", -2: "ZQFP_E_SHAPE", -3: "ZQFP_E_ALIGN", -4: "ZQFP_E_MODE", -5: "ZQFP_E_HIP"}
+_ERR = {-1: "ZQFP_E_NULL", -2: "ZQFP_E_SHAPE", -3: "ZQFP_E_ALIGN", -4: "ZQFP_E_MODE", -5: "ZQFP_E_HIP",
+        -6: "ZQFP_E_WORKSPACE", -7: "ZQFP_E_BLOB"}
+BLOB_HEADER_BYTES = 256
 
 _lib = None
 
@@ -52,9 +55,12 @@ def lib():
         L.zqfp_gemm_workspace_bytes.restype = c.c_size_t
         L.zqfp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
         L.zqfp_w4a8_gemm.restype = c.c_int
-        L.zqfp_w4a8_gemm.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_w4a8_gemm.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, i64, c.c_int, c.c_int, p, c.c_size_t, p]
         L.zqfp_w4a8_gemm_lorc.restype = c.c_int
-        L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p,
+                                          c.c_size_t, p]
+        L.zqfp_packed_weight_check.restype = c.c_int
+        L.zqfp_packed_weight_check.argtypes = [p, i64, i64, c.c_int]
         L.zqfp_rmsnorm_quantize_act_fp8.restype = c.c_int
         L.zqfp_rmsnorm_quantize_act_fp8.argtypes = [p, p, c.c_float, i64, i64, i64, p, p, p, c.c_int, p, p]
         L.zqfp_layernorm_quantize_act_fp8.restype = c.c_int
@@ -85,7 +91,7 @@ def lib():
 
 def _check(rc):
     if rc != 0:
-        raise ZqfpError(rc, lib().zqfp_last_hip_error().decode() if rc == -5 else "")
+        raise ZqfpError(rc, lib().zqfp_last_hip_error().decode() if rc in (-5, -6) else "")
 
 
 def _ptr(t):
@@ -239,6 +245,9 @@ def pack_weight_fp4(W, G, mode):
 def unpack_codes(packed, K, N, G):
     """packed blob -> codes [K,N] uint8, exps [K/G,N] uint8, colscale [N] f32."""
     _dev(packed, torch.uint8, 1)
+    if packed.numel() != packed_weight_bytes(K, N, G) or packed.numel() == 0:
+        raise ZqfpError(-2, f"packed blob has {packed.numel()} bytes, a blob of (K={K}, N={N}, G={G}) has "
+                            f"{packed_weight_bytes(K, N, G)}")
     codes = torch.empty((K, N), dtype=torch.uint8, device=packed.device)
     exps = torch.empty((K // G, N), dtype=torch.uint8, device=packed.device)
     colscale = torch.empty((N,), dtype=torch.float32, device=packed.device)
@@ -255,32 +264,73 @@ def _workspace(M, K, N, device):
     return torch.empty((n,), dtype=torch.uint8, device=device) if n else None
 
 
-def w4a8_gemm(Xq, sx, packed, N, G, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
-    """Y [M,N] = (sx c) * (Xq . Wq)."""
+def check_gemm_args(M, K, N, G, packed_numel, workspace_numel, out_shape, out_dtype, out_stride, out_is_cuda=True):
+    """Host-side refusals of the GEMM wrappers, on plain numbers (the library cannot look into device memory
+    without a synchronization, so sizes that it takes on trust are compared here): raises ZqfpError(-2 / -6 / -4)
+    for a blob whose size is not that of (K, N, G), a workspace smaller than the query's answer, an output that
+    is not a [M, N] float32 / bfloat16 tensor with contiguous rows."""
+    need = packed_weight_bytes(K, N, G)
+    if need == 0:
+        raise ZqfpError(-2, f"(K={K}, N={N}, G={G}) outside the shape limits")
+    if packed_numel != need:
+        raise ZqfpError(-2, f"packed blob has {packed_numel} bytes, a blob of (K={K}, N={N}, G={G}) has {need}")
+    if workspace_numel is not None and workspace_numel < gemm_workspace_bytes(M, K, N):
+        raise ZqfpError(-6, f"workspace has {workspace_numel} bytes, zqfp_gemm_workspace_bytes says "
+                            f"{gemm_workspace_bytes(M, K, N)}")
+    if out_dtype not in (torch.float32, torch.bfloat16):
+        raise ZqfpError(-4, f"output dtype {out_dtype}: float32 or bfloat16")
+    if not out_is_cuda or tuple(out_shape) != (M, N) or (N > 1 and out_stride[1] != 1) or (M > 1 and out_stride[0] < N):
+        raise ZqfpError(-2, f"output must be a CUDA [M={M}, N={N}] tensor with contiguous rows")
+
+
+def packed_weight_check(packed, K, N, G):
+    """Copies the blob's header to the host (this synchronizes) and asks the library whether it is a blob of
+    (K, N, G); raises ZqfpError(-7) if not.  Meant to be called once per blob, after packing."""
+    _dev(packed, torch.uint8, 1)
+    if packed.numel() < BLOB_HEADER_BYTES:
+        raise ZqfpError(-7, "shorter than a header")
+    host = packed[:BLOB_HEADER_BYTES].cpu().numpy().tobytes()
+    _check(lib().zqfp_packed_weight_check(host, K, N, G))
+
+
+def _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace):
     _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
     M, K = Xq.shape
+    if sx.shape[0] != M:
+        raise ZqfpError(-2, "one token scale per row of Xq")
+    r = 0
+    if T is not None:
+        _dev(T, torch.float32, 2), _dev(V, torch.float16, 2)
+        r = T.shape[1]
+        if T.shape[0] != M or tuple(V.shape) != (r, N):
+            raise ZqfpError(-2, "LoRC factor shapes")
     Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    if workspace is not None:
+        _dev(workspace, torch.uint8, 1)
+    check_gemm_args(M, K, N, G, packed.numel(), None if workspace is None else workspace.numel(), Y.shape, Y.dtype,
+                    Y.stride(), Y.is_cuda)
     code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
     ws = workspace if workspace is not None else _workspace(M, K, N, Xq.device)
-    _check(lib().zqfp_w4a8_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(Y), Y.stride(0), code, accum,
-                                _ptr(ws), _stream(Xq)))
+    nws = 0 if ws is None else ws.numel()
+    if r:
+        _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
+                                         Y.stride(0), code, accum, _ptr(ws), nws, _stream(Xq)))
+    else:
+        _check(lib().zqfp_w4a8_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(Y), Y.stride(0), code, accum,
+                                    _ptr(ws), nws, _stream(Xq)))
     return Y
+
+
+def w4a8_gemm(Xq, sx, packed, N, G, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
+    """Y [M,N] = (sx c) * (Xq . Wq)."""
+    return _gemm_call(Xq, sx, packed, N, G, None, None, out_dtype, accum, out, workspace)
 
 
 def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
     """Y [M,N] = (sx c) * (Xq . Wq) + T . V."""
-    _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
-    _dev(T, torch.float32, 2), _dev(V, torch.float16, 2)
-    M, K = Xq.shape
-    r = T.shape[1]
-    if T.shape[0] != M or tuple(V.shape) != (r, N):
-        raise ZqfpError(-2, "LoRC factor shapes")
-    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
-    code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
-    ws = workspace if workspace is not None else _workspace(M, K, N, Xq.device)
-    _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
-                                     Y.stride(0), code, accum, _ptr(ws), _stream(Xq)))
-    return Y
+    if T is None or V is None:
+        raise ZqfpError(-1, "T and V are required")
+    return _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace)
 
 
 def gptq_pack_weight_fp4(W, Hinv_u, G, mode):

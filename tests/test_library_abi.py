@@ -13,9 +13,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "zqfp.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(zqfp_\w+)\s*\(", text)))
+    syms = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        syms |= set(re.findall(r"\b(zqfp_\w+)\s*\(", text))
+    return sorted(syms)
 
 
 @pytest.fixture(scope="module")
@@ -72,13 +75,68 @@ def test_argument_checks_return_error_codes_without_a_gpu(lib):
     assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 16, 128, 1, None, None) == -1
     assert lib.zqfp_pack_weight_fp4(p(a16), 128, 16, 16, 128, 1, p(a16 + 16), None) == -3
     # gemm: out dtype, rank, empty problem is a no-op
-    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 7, 0, None, None) == -4
-    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 0, 5, None, None) == -4
-    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 0, 128, p(a16), 16, 128, p(a16), 16, 0, 0, None, None) == 0
-    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, None, 16, 128, p(a16), 16, 0, 0, None, None) == -1
-    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 8, 0, 0, None, None) == -2
-    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, None, None, 8, p(a16), 16, 0, 0, None, None) == -1
-    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), p(a16), 65, p(a16), 16, 0, 0, None, None) == -2
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 7, 0, None, 0, None) == -4
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 16, 0, 5, None, 0, None) == -4
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 0, 128, p(a16), 16, 128, p(a16), 16, 0, 0, None, 0, None) == 0
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, None, 16, 128, p(a16), 16, 0, 0, None, 0, None) == -1
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), 8, 0, 0, None, 0, None) == -2
+    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, None, None, 8, p(a16), 16, 0, 0, None, 0, None) == -1
+    assert lib.zqfp_w4a8_gemm_lorc(p(a16), p(a16), 1, 128, p(a16), 16, 128, p(a16), p(a16), 65, p(a16), 16, 0, 0, None, 0, None) == -2
+    # a workspace that is given must be as large as the query says (here: one 64 x 128 tile, K split 4 ways)
+    need = lib.zqfp_gemm_workspace_bytes(64, 4096, 128)
+    assert need > 0
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 64, 4096, p(a16), 128, 128, p(a16), 128, 0, 0, p(a16), need - 1, None) == -6
+    assert b"workspace" in lib.zqfp_last_hip_error()
+    assert lib.zqfp_w4a8_gemm(p(a16), p(a16), 16, 28672, p(a16), 8192, 128, p(a16), 8192, 0, 0, p(a16), 1 << 20, None) == -6
+    # shape limits of the layout itself
+    assert lib.zqfp_packed_weight_bytes(128 * 4096, 16, 128 * 16) == 0   # 4096 k-tiles: beyond the limit
+    assert lib.zqfp_packed_weight_bytes(128 * 4095, 16, 128 * 21) > 0
+
+
+def test_packed_weight_check_reads_a_host_copy_of_the_header(lib):
+    """Header fields as the packer writes them (magic 'ZQF4', version, K, N, Np, G, Gs, mode, ngs, ngq, pad,
+    four section offsets): accepted for its own (K, N, G), refused for any other and after any damage."""
+    import struct
+    K, N, G = 512, 200, 64
+    total = lib.zqfp_packed_weight_bytes(K, N, G)
+    Np = 208
+    off_codes = 256
+    off_exps = off_codes + Np * K // 2
+    ngs = K // 64
+    ngq = (ngs + 3) // 4
+    off_cs = (off_exps + (Np // 16) * ngq * 64 + 255) // 256 * 256
+    assert total == (off_cs + 4 * Np + 255) // 256 * 256
+    hdr = struct.pack("<IIqqqiiiiiIQQQQ", 0x3446515A, 1, K, N, Np, G, 64, 2, ngs, ngq, 0, off_codes, off_exps, off_cs, total)
+    hdr = hdr + bytes(256 - len(hdr))
+    chk = lambda h, k, n, g: lib.zqfp_packed_weight_check(h, k, n, g)
+    assert chk(hdr, K, N, G) == 0
+    assert chk(hdr, K, N, 128) == -7 and chk(hdr, K, N + 1, G) == -7 and chk(hdr, 2 * K, N, G) == -7
+    assert chk(hdr, K, N, 48) == -2 and chk(None, K, N, G) == -1
+    assert chk(b"\0" * 256, K, N, G) == -7
+    for pos in (0, 4, 8, 16, 32, 40, 56, 80):
+        bad = bytearray(hdr)
+        bad[pos] ^= 1
+        assert chk(bytes(bad), K, N, G) == -7, pos
+
+
+def test_binding_refuses_sizes_the_library_must_take_on_trust():
+    """The wrappers compare what the C side cannot (it never reads device memory on the host): blob size against
+    (K, N, G), workspace size against the query, the output's shape, dtype and row contiguity."""
+    import torch
+    K, N, G, M = 4096, 128, 128, 64
+    nb = zqfp.packed_weight_bytes(K, N, G)
+    ok = dict(M=M, K=K, N=N, G=G, packed_numel=nb, workspace_numel=None, out_shape=(M, N), out_dtype=torch.float32,
+              out_stride=(N, 1))
+    zqfp.check_gemm_args(**ok)
+    zqfp.check_gemm_args(**{**ok, "workspace_numel": zqfp.gemm_workspace_bytes(M, K, N)})
+    zqfp.check_gemm_args(**{**ok, "out_stride": (N + 8, 1), "out_dtype": torch.bfloat16})
+    for change, code in (({"packed_numel": nb - 256}, -2), ({"G": 256}, -2), ({"N": 144}, -2), ({"G": 48}, -2),
+                         ({"workspace_numel": zqfp.gemm_workspace_bytes(M, K, N) - 4}, -6),
+                         ({"out_dtype": torch.float16}, -4), ({"out_shape": (M, N + 1)}, -2),
+                         ({"out_stride": (N, 2)}, -2), ({"out_stride": (N - 1, 1)}, -2), ({"out_is_cuda": False}, -2)):
+        with pytest.raises(zqfp.ZqfpError) as e:
+            zqfp.check_gemm_args(**{**ok, **change})
+        assert e.value.code == code, change
 
 
 def test_build_rejects_spills_in_hand_scheduled_kernels():
