@@ -51,8 +51,7 @@ extern "C" {
 #define ZQFP_E_ALIGN (-3) /* pointer or leading dimension alignment */
 #define ZQFP_E_MODE (-4)  /* unknown scale mode / output dtype / accumulation mode */
 #define ZQFP_E_HIP (-5)   /* a HIP call failed; see zqfp_last_hip_error() */
-#define ZQFP_E_WORKSPACE (-6) /* workspace given but smaller than the query says,
-                                 or (static variant) larger than the built-in array */
+#define ZQFP_E_WORKSPACE (-6) /* workspace given but smaller than the query says */
 #define ZQFP_E_BLOB (-7)  /* zqfp_packed_weight_check: not a blob of this (K, N, G) */
 
 #define ZQFP_SCALE_M1 1 /* S^ = 2^ceil(log2 S) per group               */

@@ -36,6 +36,20 @@ int zqfp_probe_stream_read(const void *src, int64_t bytes, void *sink,
 int zqfp_probe_mfma(const void *operands, void *sink, int iters,
                     int workgroups, void *stream);
 
+/*
+ * zqfp_probe_force_tile_plan -- tuning hook for sweeps and tests: every following
+ * zqfp_w4a8_gemm* call with more than 16 tokens (and zqfp_gemm_workspace_bytes,
+ * which must agree with it) uses bm x bn output tiles, `kg` wave groups per
+ * workgroup and `ksplit` slices of K (1 = none) instead of planning them from
+ * the problem size.  Tile shapes: 64x128, 64x192, 64x256, 128x128, 128x192,
+ * 128x256, 256x256; kg 1, or 2 with 64-row tiles (it then needs an even number
+ * of 128-wide k-tiles per slice, else one group runs); ksplit 1..64 (capped at
+ * the number of k-tiles).  (0, 0, 0, 0) returns to automatic planning.
+ * Process-wide, not meant for concurrent use with GEMM calls of other threads.
+ * Returns ZQFP_OK or ZQFP_E_SHAPE.
+ */
+int zqfp_probe_force_tile_plan(int bm, int bn, int ksplit, int kg);
+
 #ifdef __cplusplus
 }
 #endif

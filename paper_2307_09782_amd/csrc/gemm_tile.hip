@@ -24,6 +24,8 @@
 // chunks (whole cache lines on the way in, conflict-free 16 B/lane operand
 // reads on the way out); the weight tile already has its operand order in
 // memory and is copied as is.
+#include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "zqfp_internal.h"
@@ -264,9 +266,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     auto as_v8i = [](const u32x4& p, const u32x4& q) {
         return (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
     };
+    // The band split of the shared header in four operations instead of five for the small wave tiles: the two
+    // constants of the byte selector live in registers (one scalar, one vector), so that "and" and "or" are one
+    // three-operand instruction.  Plain vector operations take matrix-pipe time (about 3.5 cycles each beyond
+    // three per matrix instruction, measured on register-only loops), and with few column blocks per wave the
+    // split is most of them.  The large wave tiles have no register to spare and stay below that threshold anyway.
+    constexpr bool kSplit4 = WTM * WTN <= 16;
+    uint32_t k_sel_base = 0x03020100u, k_sel_mask = 0x04040404u;
+    if constexpr (kSplit4) {
+        asm volatile("" : "+v"(k_sel_base));  // opaque: keeps the constants in registers
+        asm volatile("" : "+s"(k_sel_mask));
+    }
     auto split_in_place = [&](v8i& frag, int d) __attribute__((always_inline)) {  // dword d of frag -> upper band into fx, lower band stays
+        const uint32_t x = (uint32_t)frag[d];
         uint32_t h, l;
-        split_exponent_bands_dword((uint32_t)frag[d], h, l);
+        if constexpr (kSplit4) {
+            uint32_t sel;
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(sel) : "v"(x >> 4), "s"(k_sel_mask), "v"(k_sel_base));
+            l = __builtin_amdgcn_perm(0u, x, sel);
+            h = x ^ l;
+        } else {
+            split_exponent_bands_dword(x, h, l);
+        }
         fx[d] = (int)h;
         frag[d] = (int)l;
     };
@@ -585,6 +606,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
     }
 }
 
+
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                       void* Y, int64_t ldy, int out_dtype, int ksplit, int kslice, float* partial, hipStream_t s)
@@ -611,34 +633,35 @@ template <bool EXACT>
 hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                        void* Y, int64_t ldy, int out_dtype, void* workspace, hipStream_t s)
 {
-    TilePlan p = plan_tiles(M, L.Np, L.nkt);
+    TilePlan p = effective_tile_plan(M, L.Np, L.nkt);
     if (workspace == nullptr) { p.ksplit = 1; p.kslice = (int)L.nkt; }  // no room for partial tiles: one slice
     float* ws = static_cast<float*>(workspace);
-    if (p.bm == 128 && p.bn == 192)
-        return launch_cfg<4, 6, 2, 2, 2, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 128 && p.bn == 256)
-        return launch_cfg<4, 8, 2, 2, 2, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 256) return launch_cfg<4, 8, 4, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    if (p.bm == 128) return launch_cfg<4, 4, 2, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s);
-    // at most one workgroup per compute unit: two wave groups per workgroup take the k-tiles in turn (two waves
-    // per SIMD instead of one; 9-12 % faster at LLaMA-70B FFN M = 32, 64), which needs an even number of them in
-    // every slice.  With more workgroups than compute units the one-group form runs up to three per compute
-    // unit and is the faster one.
-    const int64_t tiles = ((M + 63) / 64) * ((L.Np + 127) / 128);
-    if (p.ksplit >= 2) {  // half as many slices (of even length), two wave groups each: half the partial tiles to add up
+#define ZQ_TILE(WTM, WTN, WM, WN, NST, KG) \
+    return launch_cfg<WTM, WTN, WM, WN, NST, KG, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s)
+    if (p.bm == 256) ZQ_TILE(4, 8, 4, 2, 3, 1);
+    if (p.bm == 128 && p.bn == 256) ZQ_TILE(4, 8, 2, 2, 2, 1);
+    if (p.bm == 128 && p.bn == 192) ZQ_TILE(4, 6, 2, 2, 2, 1);
+    if (p.bm == 128) ZQ_TILE(4, 4, 2, 2, 3, 1);
+    // 64-row tiles.  Two wave groups need an even number of k-tiles in every slice.
+    if (p.ksplit >= 2 && !p.forced) {  // half as many slices (of even length), two wave groups each: half the partial tiles to add up
+        const int64_t tiles = ((M + 63) / 64) * ((L.Np + 127) / 128);
         const int want = (p.ksplit + 1) / 2;
         int kslice = (int)((L.nkt + want - 1) / want);
         kslice += kslice & 1;
         const int ksplit = (int)((L.nkt + kslice - 1) / kslice);
         const int tail = (int)L.nkt - (ksplit - 1) * kslice;
-        if (tiles * ksplit <= 256 && tail > 0 && tail % 2 == 0) { p.ksplit = ksplit; p.kslice = kslice; }
+        if (tiles * ksplit <= 256 && tail > 0 && tail % 2 == 0) { p.ksplit = ksplit; p.kslice = kslice; p.kg = 2; }
     }
-    const int64_t units = tiles * p.ksplit;
-    const int last = (int)L.nkt - (p.ksplit - 1) * p.kslice;
-    if (units <= 256 && p.kslice % 2 == 0 && last % 2 == 0)
-        return launch_cfg<2, 4, 2, 2, 3, 2, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
-    return launch_cfg<2, 4, 2, 2, 3, 1, EXACT>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, p.ksplit, p.kslice, ws, s);
+    const bool even_slices = p.kslice % 2 == 0 && ((int)L.nkt - (p.ksplit - 1) * p.kslice) % 2 == 0;
+    const bool two_groups = p.kg == 2 && even_slices;
+    if (p.bn == 256) { if (two_groups) ZQ_TILE(2, 8, 2, 2, 3, 2); ZQ_TILE(2, 8, 2, 2, 3, 1); }
+    if (p.bn == 192) { if (two_groups) ZQ_TILE(2, 6, 2, 2, 3, 2); ZQ_TILE(2, 6, 2, 2, 3, 1); }
+    if (two_groups) ZQ_TILE(2, 4, 2, 2, 3, 2);
+    ZQ_TILE(2, 4, 2, 2, 3, 1);
+#undef ZQ_TILE
 }
+
+std::atomic<uint32_t> g_forced_plan{0};  // bm | bn << 10 | ksplit << 20 | kg << 28; 0 = automatic
 
 }  // namespace
 
@@ -652,6 +675,88 @@ hipError_t launch_splitk_reduce(const float* partial, int slices, int64_t M, con
 }
 
 bool gemm_tile_supported(int64_t M, const BlobLayout& L) { return M > 16 && L.N >= 64; }
+
+// ---- planning.  Measured on LLaMA-7B / 13B / 70B and OPT shapes (exact accumulation), the time of a launch is
+// close to  3 + t * (e + s * k-tiles)  microseconds, t = the most tiles any compute unit gets: e is a tile's
+// prologue and epilogue, s its k-step.  Small tiles cost more per output (plain vector work per matrix
+// instruction grows as a wave's tile narrows, and it takes matrix-pipe time), large tiles come in coarser
+// rounds.  A compute unit that holds a single four-wave workgroup has one wave per SIMD and nothing to fill
+// its stalls with: 1.3 times slower.  The planner takes the cheapest.
+struct TileKind {
+    int bm, bn, kg;
+    float e, s;
+};
+constexpr TileKind kTileKinds[] = {
+    {64, 128, 2, 3.3f, 0.406f},   // two wave groups: one workgroup per compute unit, so at most 256 tiles
+    {64, 192, 2, 4.3f, 0.570f},
+    {64, 256, 2, 5.3f, 0.666f},
+    {64, 128, 1, 3.5f, 0.325f},
+    {64, 192, 1, 4.5f, 0.434f},
+    {64, 256, 1, 5.5f, 0.530f},
+    {128, 128, 1, 5.5f, 0.594f},
+    {128, 192, 1, 7.5f, 0.780f},
+    {128, 256, 1, 9.5f, 0.990f},
+    {256, 256, 1, 17.5f, 2.000f},
+};
+
+TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
+{
+    constexpr int64_t kCUs = 256;  // MI355X
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((Np + bn - 1) / bn); };
+    TilePlan p{64, 128, 1, 1, (int)nkt};
+    // Few output tiles, long K (down-projections at small M): even 64 x 128 tiles fill less than a third of the
+    // chip, so K is cut into slices of at least 8 k-steps.
+    {
+        const int64_t slots = 2 * kCUs, nt = tiles(64, 128);
+        int64_t want = slots / nt;
+        if (want > 16) want = 16;
+        if (want > nkt / 8) want = nkt / 8;
+        if (want >= 3) {
+            p.kslice = (int)((nkt + want - 1) / want);
+            p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
+            return p;
+        }
+    }
+    // Many rounds of large tiles: 128 x 256, two workgroups per compute unit that fill each other's gaps.
+    const int64_t n256 = tiles(256, 256);
+    if (n256 >= kCUs * 3 / 2) { p.bm = 128; p.bn = 256; return p; }
+    float best = 0.f;
+    bool have = false;
+    for (const TileKind& k : kTileKinds) {
+        const int64_t t = tiles(k.bm, k.bn);
+        if (k.kg == 2 && (t > kCUs || (nkt & 1))) continue;
+        if (k.bm > 64 && M <= 64) continue;
+        const float per_cu = (float)((t + kCUs - 1) / kCUs);
+        const bool lone_waves = t <= kCUs && k.kg == 1 && k.bm < 256;
+        const float cost = 3.0f + per_cu * (k.e + k.s * (float)nkt) * (lone_waves ? 1.3f : 1.0f);
+        if (!have || cost < best) { best = cost; have = true; p.bm = k.bm; p.bn = k.bn; p.kg = k.kg; }
+    }
+    return p;
+}
+
+bool force_tile_plan(int bm, int bn, int ksplit, int kg)
+{
+    if (bm == 0 && bn == 0 && ksplit == 0) { g_forced_plan.store(0); return true; }
+    const bool shape_ok = (bm == 64 && (bn == 128 || bn == 192 || bn == 256)) ||
+                          (bm == 128 && (bn == 128 || bn == 192 || bn == 256)) || (bm == 256 && bn == 256);
+    if (!shape_ok || ksplit < 1 || ksplit > 64 || kg < 1 || kg > 2 || (kg == 2 && bm != 64)) return false;
+    g_forced_plan.store((uint32_t)bm | ((uint32_t)bn << 10) | ((uint32_t)ksplit << 20) | ((uint32_t)kg << 28));
+    return true;
+}
+
+TilePlan effective_tile_plan(int64_t M, int64_t Np, int64_t nkt)
+{
+    const uint32_t f = g_forced_plan.load(std::memory_order_relaxed);
+    if (f == 0) return plan_tiles(M, Np, nkt);
+    TilePlan p;
+    p.bm = (int)(f & 1023u); p.bn = (int)((f >> 10) & 1023u);
+    p.kg = (int)(f >> 28);
+    const int want = (int)std::min<int64_t>((int64_t)((f >> 20) & 255u), nkt);
+    p.kslice = (int)((nkt + want - 1) / want);
+    p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
+    p.forced = true;
+    return p;
+}
 
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
                             Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s)

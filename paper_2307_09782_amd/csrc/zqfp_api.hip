@@ -30,7 +30,7 @@ size_t gemm_workspace_need(int64_t M, int64_t K, int64_t N)
         return d.chunks > 1 ? (size_t)d.chunks * (size_t)M * (size_t)Np * sizeof(float) : 0;
     }
     if (N < 64) return 0;
-    const zqfp::TilePlan p = zqfp::plan_tiles(M, Np, K / 128);
+    const zqfp::TilePlan p = zqfp::effective_tile_plan(M, Np, K / 128);
     return p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)Np * sizeof(float) : 0;
 }
 
@@ -260,6 +260,11 @@ int zqfp_probe_stream_read(const void* src, int64_t bytes, void* sink, int workg
     hipError_t e = zqfp::launch_probe_read(src, bytes, static_cast<uint32_t*>(sink), workgroups,
                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_probe_force_tile_plan(int bm, int bn, int ksplit, int kg)
+{
+    return zqfp::force_tile_plan(bm, bn, ksplit, kg) ? ZQFP_OK : ZQFP_E_SHAPE;
 }
 
 int zqfp_probe_mfma(const void* operands, void* sink, int iters, int workgroups, void* stream)

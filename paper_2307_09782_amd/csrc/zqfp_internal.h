@@ -170,52 +170,20 @@ __device__ inline float e2m1_value(uint32_t code)
     return (code & 8u) ? -v : v;
 }
 
-// Tile shape and K-split of the tiled GEMM for a problem size (the launcher and the workspace query
-// must agree).  Counted in 256 x 256 tiles: with at least ~1.5 per compute unit (256 of them) the
-// kernel runs 128 x 256 tiles, 4 waves and two LDS stages, two workgroups per compute unit that fill
-// each other's prologue, epilogue and barrier gaps; with three quarters to one per compute unit, one
-// round of 256 x 256 tiles (8 waves, three LDS stages, one workgroup per compute unit); else
-// 128 x 128 (4 waves, two workgroups per compute unit) if there are enough of those; else 64 x 128,
-// which also serves 16 < M <= 64, where the kernel is a weight stream.  When even those tiles fill
-// less than a third of the chip (few output channels, long K: down-projections at small M), K is cut
-// into `ksplit` slices of `kslice` k-tiles, each tile-slice goes to its own workgroup, and the float32
-// partial tiles meet in a workspace (ksplit * M * Np floats) that a second kernel sums in fixed order.
+// Tile shape, wave groups and K-split of the tiled GEMM for a problem (the launcher and the workspace query
+// must agree; gemm_tile.hip plans them).  `kg` wave groups of four waves share a tile and take its k-tiles in
+// turn (two waves per SIMD from one workgroup per compute unit).  When even the smallest tiles fill less than a
+// third of the chip (few output channels, long K: down-projections at small M), K is cut into `ksplit` slices
+// of `kslice` k-tiles, each tile-slice goes to its own workgroup, and the float32 partial tiles meet in a
+// workspace (ksplit * M * Np floats) that a second kernel sums in fixed order.
 struct TilePlan {
     int bm, bn;       // tile shape
+    int kg;           // wave groups per workgroup (1 or 2)
     int ksplit;       // number of K slices (1: none)
     int kslice;       // k-tiles per slice
+    bool forced = false;  // set through the tuning hook (zqfp_probe_force_tile_plan), not planned
 };
-inline TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
-{
-    constexpr int64_t kCUs = 256;  // MI355X
-    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((Np + bn - 1) / bn); };
-    TilePlan p{64, 128, 1, (int)nkt};
-    const int64_t n256 = tiles(256, 256);
-    if (n256 >= kCUs * 3 / 2) { p.bm = 128; p.bn = 256; return p; }
-    if (n256 <= kCUs && n256 * 4 >= kCUs * 3) {
-        // a single round of 256 x 256 tiles that leaves compute units idle: 128 x 192 tiles, two workgroups per
-        // compute unit, when they make (nearly) a whole round of 512 (7B QKV at M = 1024: 12 % faster)
-        const int64_t t192 = tiles(128, 192);
-        if (n256 < kCUs && t192 <= 2 * kCUs && t192 * 8 >= 2 * kCUs * 7) { p.bm = 128; p.bn = 192; return p; }
-        p.bm = 256; p.bn = 256;
-        return p;
-    }
-    // 128 x 128 tiles run two workgroups per compute unit (rounds of 512 tiles), 64 x 128 tiles three (rounds of
-    // 768): up to a round and a half of the small tiles they are the faster ones (7B QKV at M = 512, 768: 9 and 7 %),
-    // unless their last round would be nearly empty or the larger tiles come out as whole rounds
-    const int64_t t128 = tiles(128, 128), t64 = tiles(64, 128);
-    const bool small_fit = t64 <= 1152 && (t64 % 768 == 0 || t64 % 768 >= 256) && t128 % 512 != 0;
-    if (M > 64 && t128 >= 384 && !small_fit) { p.bm = 128; p.bn = 128; return p; }
-    const int64_t slots = 2 * kCUs, nt = tiles(64, 128);
-    int64_t want = slots / nt;
-    if (want > 16) want = 16;
-    if (want > nkt / 8) want = nkt / 8;  // a slice is at least 8 k-steps
-    if (want >= 3) {
-        p.kslice = (int)((nkt + want - 1) / want);
-        p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
-    }
-    return p;
-}
+TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt);
 
 // The decode GEMM keeps a wave's activation fragments in registers, at most 8 k-tiles per wave and
 // 64 per workgroup.  A longer K is cut into `chunks` pieces of `len` k-tiles; a workgroup serves one
@@ -262,6 +230,11 @@ hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const
                             const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                             int accum, void* workspace, hipStream_t s);
 bool gemm_tile_supported(int64_t M, const BlobLayout& L);
+// The plan the tiled form runs for a problem: plan_tiles, unless the tuning hook has fixed one (tile shape and
+// number of K slices for every following call; 0, 0, 0 returns to automatic planning; false = not a shape the kernel has).
+TilePlan effective_tile_plan(int64_t M, int64_t Np, int64_t nkt);
+bool force_tile_plan(int bm, int bn, int ksplit, int kg);
+
 // workspace: plan_decode(nkt).chunks * M * Np floats when K has more than 64 k-tiles (else unused)
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,

@@ -83,6 +83,8 @@ def lib():
         L.zqfp_gptq_pack_weight_fp4.argtypes = [p, i64, i64, i64, p, c.c_int, c.c_int, p, p, p]
         L.zqfp_probe_stream_read.restype = c.c_int
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
+        L.zqfp_probe_force_tile_plan.restype = c.c_int
+        L.zqfp_probe_force_tile_plan.argtypes = [c.c_int, c.c_int, c.c_int, c.c_int]
         L.zqfp_probe_mfma.restype = c.c_int
         L.zqfp_probe_mfma.argtypes = [p, p, c.c_int, c.c_int, p]
         _lib = L
@@ -305,12 +307,13 @@ def _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace):
         if T.shape[0] != M or tuple(V.shape) != (r, N):
             raise ZqfpError(-2, "LoRC factor shapes")
     Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
-    if workspace is not None:
+    no_ws = workspace is False  # run without the K-split (the library accepts NULL)
+    if workspace is not None and not no_ws:
         _dev(workspace, torch.uint8, 1)
-    check_gemm_args(M, K, N, G, packed.numel(), None if workspace is None else workspace.numel(), Y.shape, Y.dtype,
-                    Y.stride(), Y.is_cuda)
+    check_gemm_args(M, K, N, G, packed.numel(), None if (workspace is None or no_ws) else workspace.numel(), Y.shape,
+                    Y.dtype, Y.stride(), Y.is_cuda)
     code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
-    ws = workspace if workspace is not None else _workspace(M, K, N, Xq.device)
+    ws = None if no_ws else workspace if workspace is not None else _workspace(M, K, N, Xq.device)
     nws = 0 if ws is None else ws.numel()
     if r:
         _check(lib().zqfp_w4a8_gemm_lorc(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y),
@@ -322,7 +325,8 @@ def _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace):
 
 
 def w4a8_gemm(Xq, sx, packed, N, G, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
-    """Y [M,N] = (sx c) * (Xq . Wq)."""
+    """Y [M,N] = (sx c) * (Xq . Wq).  workspace: None = allocated here when the shape needs one, a uint8 tensor of
+    at least gemm_workspace_bytes(M, K, N) bytes, or False = none (K is then not split)."""
     return _gemm_call(Xq, sx, packed, N, G, None, None, out_dtype, accum, out, workspace)
 
 
@@ -385,3 +389,9 @@ def probe_mfma(operands, sink, iters, workgroups):
         raise ZqfpError(-2, "probe buffers too small")
     _check(lib().zqfp_probe_mfma(_ptr(operands), _ptr(sink), iters, workgroups, _stream(operands)))
     return 2.0 * 16 * 16 * 128 * 32 * 8 * iters * workgroups
+
+
+def probe_force_tile_plan(bm=0, bn=0, ksplit=0, kg=1):
+    """Tuning hook: fix tile shape, wave groups and number of K slices of the tiled GEMM for the calls that follow
+    (0, 0, 0 = plan automatically again)."""
+    _check(lib().zqfp_probe_force_tile_plan(bm, bn, ksplit, kg if bm else 0))
