@@ -51,7 +51,8 @@ extern "C" {
 #define ZQFP_E_ALIGN (-3) /* pointer or leading dimension alignment */
 #define ZQFP_E_MODE (-4)  /* unknown scale mode / output dtype / accumulation mode */
 #define ZQFP_E_HIP (-5)   /* a HIP call failed; see zqfp_last_hip_error() */
-#define ZQFP_E_WORKSPACE (-6) /* workspace given but smaller than the query says */
+#define ZQFP_E_WORKSPACE (-6) /* workspace given but smaller than the query says,
+                                 or (static variant) larger than the built-in array */
 #define ZQFP_E_BLOB (-7)  /* zqfp_packed_weight_check: not a blob of this (K, N, G) */
 
 #define ZQFP_SCALE_M1 1 /* S^ = 2^ceil(log2 S) per group               */
@@ -363,6 +364,37 @@ int zqfp_w4a8_gemm_lorc(const uint8_t *Xq, const float *sx, int64_t M, int64_t K
                         const float *T, const void *V, int r,
                         void *Y, int64_t ldy, int out_dtype, int accum,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * w4a8_gemm_lorc_static -- zqfp_w4a8_gemm_lorc for callers that cannot allocate
+ * device memory or pass a workspace along: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace (r = 0, T = V = NULL gives zqfp_w4a8_gemm); same kernels, same
+ * results bit for bit.  Where the other call would hand float32 partial
+ * results through the caller's workspace (K-split of few tiles, K beyond 64
+ * k-tiles at M <= 16), this one hands them through an array that is part of
+ * the library's device image: ZQFP_STATIC_SCRATCH_BYTES bytes, which every GPU
+ * that runs the library holds until the process ends.  The call allocates and
+ * frees nothing.
+ *
+ *   - zqfp_gemm_workspace_bytes(M, K, N) > ZQFP_STATIC_SCRATCH_BYTES is refused
+ *     with ZQFP_E_WORKSPACE (text in zqfp_last_hip_error()); nothing is enqueued.
+ *   - The array's device address is looked up on the first call on a device
+ *     that needs it (hipGetSymbolAddress, with that device current): make that
+ *     first call, and the first call of each new shape class (one-time kernel
+ *     attributes), outside graph capture.
+ *   - All calls on one GPU share the array.  Nothing in it needs to start at
+ *     zero (every partial result that is read has been written by the same
+ *     call), but calls that overlap in time on one GPU -- different streams, or
+ *     graphs replayed concurrently -- race on it: serialise them, or use the
+ *     workspace form for all but one.
+ */
+#define ZQFP_STATIC_SCRATCH_BYTES (32u << 20)
+int zqfp_w4a8_gemm_lorc_static(const uint8_t *Xq, const float *sx, int64_t M,
+                               int64_t K, const void *packed, int64_t N, int G,
+                               const float *T, const void *V, int r,
+                               void *Y, int64_t ldy, int out_dtype, int accum,
+                               void *stream);
 
 #ifdef __cplusplus
 }

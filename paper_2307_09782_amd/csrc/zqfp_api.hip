@@ -4,6 +4,7 @@
 #include "../../include/zqfp_probe.h"
 
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "zqfp_internal.h"
@@ -88,6 +89,40 @@ int quantize_common(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* X
 }
 
 const uint16_t* u16(const void* p) { return static_cast<const uint16_t*>(p); }
+
+// ---- the built-in scratch array of zqfp_w4a8_gemm_lorc_static.  Every device that loads this library holds
+// its own copy at its own address until the process ends.  In host code the array's NAME is only a handle
+// for hipGetSymbolAddress: the device address is asked for once per device, with that device current, and
+// from then on only that address is used (kernel arguments take it as they take a caller's workspace).
+static __device__ __align__(256) unsigned char scratch[ZQFP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device; guarded by g_scratch_mutex
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_last_error = "device ordinal beyond the per-device table of the static scratch array";
+        return ZQFP_E_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (p == nullptr) {
+            g_last_error = "hipGetSymbolAddress returned no address for the static scratch array";
+            return ZQFP_E_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZQFP_OK;
+}
 
 }  // namespace
 
@@ -206,6 +241,26 @@ int zqfp_w4a8_gemm_lorc(const uint8_t* Xq, const float* sx, int64_t M, int64_t K
                         void* workspace, size_t workspace_bytes, void* stream)
 {
     return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, workspace_bytes, stream);
+}
+
+int zqfp_w4a8_gemm_lorc_static(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N,
+                               int G, const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype,
+                               int accum, void* stream)
+{
+    const size_t need = gemm_workspace_need(M, K, N);
+    if (need > (size_t)ZQFP_STATIC_SCRATCH_BYTES) {
+        g_last_error = "partial results of this (M, K, N) need " + std::to_string(need) +
+                       " bytes, the built-in scratch array has " + std::to_string((size_t)ZQFP_STATIC_SCRATCH_BYTES) +
+                       ": use zqfp_w4a8_gemm_lorc with a workspace";
+        return ZQFP_E_WORKSPACE;
+    }
+    void* ws = nullptr;
+    if (need > 0) {  // shapes without a K-split never touch the array
+        const int rc = static_scratch(&ws);
+        if (rc != ZQFP_OK) return rc;
+    }
+    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, ws, ws ? (size_t)ZQFP_STATIC_SCRATCH_BYTES : 0,
+                       stream);
 }
 
 size_t zqfp_lorc_workspace_bytes(int64_t K, int64_t N, int r)

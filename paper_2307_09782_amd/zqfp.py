@@ -59,6 +59,8 @@ def lib():
         L.zqfp_w4a8_gemm_lorc.restype = c.c_int
         L.zqfp_w4a8_gemm_lorc.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p,
                                           c.c_size_t, p]
+        L.zqfp_w4a8_gemm_lorc_static.restype = c.c_int
+        L.zqfp_w4a8_gemm_lorc_static.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p]
         L.zqfp_packed_weight_check.restype = c.c_int
         L.zqfp_packed_weight_check.argtypes = [p, i64, i64, c.c_int]
         L.zqfp_rmsnorm_quantize_act_fp8.restype = c.c_int
@@ -322,6 +324,27 @@ def _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace):
         _check(lib().zqfp_w4a8_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(Y), Y.stride(0), code, accum,
                                     _ptr(ws), nws, _stream(Xq)))
     return Y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def w4a8_gemm_lorc_static(Xq, sx, packed, N, G, out, T=None, V=None, accum=ACCUM_EXACT):
+    """zqfp_w4a8_gemm_lorc_static: the GEMM (with LoRC when T, V are given) into the caller's `out`, partial
+    results through the library's built-in scratch array; the call allocates nothing on either side."""
+    _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
+    M, K = Xq.shape
+    r = 0
+    if T is not None:
+        _dev(T, torch.float32, 2), _dev(V, torch.float16, 2)
+        r = T.shape[1]
+        if T.shape[0] != M or tuple(V.shape) != (r, N):
+            raise ZqfpError(-2, "LoRC factor shapes")
+    check_gemm_args(M, K, N, G, packed.numel(), None, out.shape, out.dtype, out.stride(), out.is_cuda)
+    code = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    _check(lib().zqfp_w4a8_gemm_lorc_static(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(out),
+                                            out.stride(0), code, accum, _stream(Xq)))
+    return out
 
 
 def w4a8_gemm(Xq, sx, packed, N, G, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, workspace=None):
