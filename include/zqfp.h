@@ -366,6 +366,31 @@ int zqfp_w4a8_gemm_lorc(const uint8_t *Xq, const float *sx, int64_t M, int64_t K
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * w4a8_linear -- the whole layer in one call, from bfloat16 activations:
+ * zqfp_quantize_act_fp8 followed by zqfp_w4a8_gemm(_lorc) (paper Section 3:
+ * token-wise activation quantization is chosen for latency; for a handful of
+ * tokens the quantizer's own launch is a quarter of the step).
+ *
+ *   - M <= 16, K <= 4096 and r == 0: ONE kernel.  The decode GEMM reads X
+ *     itself and quantizes it in its prologue, with the arithmetic of
+ *     zqfp_quantize_act_fp8, so Y equals the two-call sequence bit for bit.
+ *     Xq and sx are optional outputs here (NULL: not written).
+ *   - otherwise: the two calls, enqueued one after the other; Xq, sx (and T
+ *     when r > 0) must then be given, as the buffers between them.
+ *
+ *   X    [M, K] bfloat16, row stride ldx (multiple of 8), 16-byte aligned   (in)
+ *   U    [K, r] binary16 or NULL with r == 0;  V  [r, N] binary16          (in)
+ *   Xq   [M, K] uint8, sx [M] float32, T [M, r] float32                     (out)
+ *   Y, workspace, other arguments and errors as for zqfp_w4a8_gemm_lorc.
+ */
+int zqfp_w4a8_linear(const void *X, int64_t ldx, int64_t M, int64_t K,
+                     const void *packed, int64_t N, int G,
+                     const void *U, const void *V, int r,
+                     uint8_t *Xq, float *sx, float *T,
+                     void *Y, int64_t ldy, int out_dtype, int accum,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * w4a8_gemm_lorc_static -- zqfp_w4a8_gemm_lorc for callers that cannot allocate
  * device memory or pass a workspace along: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments without the

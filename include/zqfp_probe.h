@@ -50,6 +50,13 @@ int zqfp_probe_mfma(const void *operands, void *sink, int iters,
  */
 int zqfp_probe_force_tile_plan(int bm, int bn, int ksplit, int kg);
 
+/*
+ * zqfp_probe_force_decode_waves -- tuning hook: 8 (default) or 16 waves per
+ * workgroup of the decode GEMM (at most 16 tokens) where K <= 4096.
+ * Process-wide.  Returns ZQFP_OK or ZQFP_E_SHAPE.
+ */
+int zqfp_probe_force_decode_waves(int nw);
+
 #ifdef __cplusplus
 }
 #endif

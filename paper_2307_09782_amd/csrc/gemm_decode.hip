@@ -26,14 +26,30 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // NW: waves per workgroup (8 or 16); KPW: k-tiles per wave (K / 128 / NW, rounded up); NB: fragment
 // buffers, i.e. NB - 1 strips in flight behind the one being multiplied.  One workgroup per compute
 // unit: NW / 4 waves per SIMD.
-template <int NW, int KPW, int NB, bool EXACT, bool LR>
+// FUSED: the activations arrive as bfloat16 and are quantized here, token-wise to E4M3 (paper Section 3), in the
+// same binary32 sequence as the stand-alone quantizer: every workgroup reads the M x K bfloat16 rows once
+// (wave w the slices of its own k-tiles), the row maxima meet in LDS, and each wave encodes its own fragments in
+// registers.  One kernel instead of two for a decode step; workgroup 0 also writes the codes and scales out
+// when the caller asks for them.
+struct FusedIn {
+    const uint16_t* X;  // [M, K] bf16, row stride ldx
+    int64_t ldx;
+    uint8_t* Xq_out;    // [M, K] E4M3 codes, or null
+    float* sx_out;      // [M], or null
+};
+
+template <int NW, int KPW, int NB, bool EXACT, bool LR, bool FUSED = false>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void k_gemm_decode(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int M, const uint8_t* __restrict__ blob, BlobLayout L,
-    Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len, float* __restrict__ partial)
+    Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len, float* __restrict__ partial,
+    FusedIn fin)
 {
     constexpr int kWaves = NW;
     constexpr bool HI_LDS = EXACT && KPW >= 8;
+    static_assert(!FUSED || (KPW <= 4 && !LR), "the fused form keeps a wave's bfloat16 slices in registers and has no LoRC");
     __shared__ float s_red[2][kWaves][64][4];
+    __shared__ uint32_t s_rowmax[FUSED ? kWaves : 1][16];
+    __shared__ float s_scale[FUSED ? 16 : 1];
     extern __shared__ __attribute__((aligned(16))) uint8_t s_hi[];  // HI_LDS: NW * KPW * 2048 bytes
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -59,6 +75,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     // never stored), a k-tile past the end repeats the last one and is zeroed further down, once
     // the first strips' weight loads have been issued behind these.
     u32x4 ax0[KPW], ax1[KPW];
+    uint4 xb[FUSED ? KPW : 1][4];  // FUSED: the lane's 32 bfloat16 of k-tile u (k = 16 lb + [0,16) and 64 + 16 lb + [0,16))
     // The fragments are filled from ax0/ax1 below.  In the exact mode they are split into their two
     // exponent bands once (they serve every strip): afr holds the lower band, ahi the upper one,
     // or, when 8 k-tiles per wave leave no registers for it, the wave's own slice of LDS does.
@@ -67,9 +84,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
     for (int u = 0; u < KPW; ++u) {
         const int kt = min(wave + kWaves * u, nkt - 1);
-        const uint8_t* p = Xq + (int64_t)min(col, M - 1) * L.K + (int64_t)(kt0 + kt) * 128 + 16 * lb;
-        ax0[u] = *reinterpret_cast<const u32x4*>(p);
-        ax1[u] = *reinterpret_cast<const u32x4*>(p + 64);
+        if constexpr (FUSED) {
+            const uint4* p = reinterpret_cast<const uint4*>(fin.X + (int64_t)min(col, M - 1) * fin.ldx + (int64_t)(kt0 + kt) * 128 + 16 * lb);
+            xb[u][0] = p[0]; xb[u][1] = p[1];  // k = 16 lb + [0, 16)
+            xb[u][2] = p[8]; xb[u][3] = p[9];  // 64 elements (128 bytes) further on
+        } else {
+            const uint8_t* p = Xq + (int64_t)min(col, M - 1) * L.K + (int64_t)(kt0 + kt) * 128 + 16 * lb;
+            ax0[u] = *reinterpret_cast<const u32x4*>(p);
+            ax1[u] = *reinterpret_cast<const u32x4*>(p + 64);
+        }
     }
     // stored exponent group of this lane's 32-block of its u-th k-tile (recomputed where needed:
     // a few integer operations, cheaper than holding it in registers)
@@ -98,7 +121,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int er = (tid >> 4) & 15, ec = tid & 15;
     const bool row_live = tid < 256 && er < M;
     const int rk = lorc.r;
-    float sx_r = raw ? 1.0f : sx[min(er, M - 1)], t_r[RMAX];  // raw: scales are applied when the chunks are added up
+    float sx_r = (raw || FUSED) ? 1.0f : sx[min(er, M - 1)], t_r[RMAX];  // raw: scales are applied when the chunks are added up; FUSED: set below
 #pragma unroll
     for (int j = 0; j < RMAX; ++j) t_r[j] = 0.f;
     if constexpr (LR) {
@@ -193,6 +216,40 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     auto strip_of = [&](int64_t qq) { return paired ? 2 * (8 * (qq >> 1) + xcd) + (qq & 1) : qq; };
 #pragma unroll
     for (int r = 0; r < NB - 1; ++r) issue(r, strip_of(q + r * stride));
+    if constexpr (FUSED) {
+        // token maxima: this lane's, then the four lanes of its row (same lane % 16), then the waves through LDS
+        uint32_t am = 0;
+#pragma unroll
+        for (int u = 0; u < KPW; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) am = absmax_bits(am, xb[u][c]);  // duplicates of the last k-tile change nothing
+        am = max(am, (uint32_t)__shfl_xor((int)am, 16));
+        am = max(am, (uint32_t)__shfl_xor((int)am, 32));
+        if (lane < 16) s_rowmax[wave][lane] = am;
+        __syncthreads();
+        am = s_rowmax[0][col];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) am = max(am, s_rowmax[w][col]);
+        float scale, inv;
+        token_scale(am, scale, inv);
+        if (tid < 16) s_scale[tid] = scale;  // tid < 16: lane == col == row
+        const bool write_out = blockIdx.x == 0 && col < M;
+        if (write_out && fin.sx_out != nullptr && tid < 16) fin.sx_out[col] = scale;
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+            const uint2 c0 = encode8(xb[u][0], inv), c1 = encode8(xb[u][1], inv);
+            const uint2 c2 = encode8(xb[u][2], inv), c3 = encode8(xb[u][3], inv);
+            ax0[u] = (u32x4){c0.x, c0.y, c1.x, c1.y};
+            ax1[u] = (u32x4){c2.x, c2.y, c3.x, c3.y};
+            if (write_out && fin.Xq_out != nullptr && wave + kWaves * u < nkt) {
+                uint8_t* p = fin.Xq_out + (int64_t)col * L.K + (int64_t)(kt0 + wave + kWaves * u) * 128 + 16 * lb;
+                *reinterpret_cast<u32x4*>(p) = ax0[u];
+                *reinterpret_cast<u32x4*>(p + 64) = ax1[u];
+            }
+        }
+        __syncthreads();
+        sx_r = s_scale[er];
+    }
 #pragma unroll
     for (int u = 0; u < KPW; ++u) {
         const bool live = wave + kWaves * u < nkt;  // uniform
@@ -229,7 +286,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 template <int NW, int KPW, int NB>
 hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
                 const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len,
-                float* partial, hipStream_t s)
+                float* partial, const FusedIn& fin, hipStream_t s)
 {
     // LoRC operands of ranks up to 8 are held in registers
     const bool lr = lorc.r > 0 && lorc.r <= 8;
@@ -247,15 +304,24 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
             }); e != hipSuccess)
             return e;
     }
-#define ZQ_LAUNCH(EX, LR) \
-    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial)
-    if (exact) { if (lr) ZQ_LAUNCH(true, true); else ZQ_LAUNCH(true, false); }
-    else       { if (lr) ZQ_LAUNCH(false, true); else ZQ_LAUNCH(false, false); }
+#define ZQ_LAUNCH(EX, LR, FU) \
+    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR, FU>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial, fin)
+    if (fin.X != nullptr) {
+        if constexpr (KPW <= 4) {
+            if (exact) ZQ_LAUNCH(true, false, true); else ZQ_LAUNCH(false, false, true);
+        } else {
+            return hipErrorInvalidValue;  // not reached: the caller checks gemm_decode_fused_supported
+        }
+    } else if (exact) { if (lr) ZQ_LAUNCH(true, true, false); else ZQ_LAUNCH(true, false, false); }
+    else       { if (lr) ZQ_LAUNCH(false, true, false); else ZQ_LAUNCH(false, false, false); }
 #undef ZQ_LAUNCH
     return hipGetLastError();
 }
 
 }  // namespace
+
+std::atomic<int> g_decode_waves{8};  // tuning hook: waves per workgroup of the decode form (8 or 16)
+void force_decode_waves(int nw) { g_decode_waves.store(nw == 16 ? 16 : 8); }
 
 // compute units of the (single) device, asked once
 int compute_units()
@@ -282,9 +348,16 @@ bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace
     return workspace != nullptr && L.nstrips * plan_decode(L.nkt).chunks >= 1024;
 }
 
-hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
-                              Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s)
+bool gemm_decode_fused_supported(int64_t M, const BlobLayout& L, int r)
 {
+    return M >= 1 && M <= 16 && L.nkt <= 32 && r == 0;  // at most 4 k-tiles per wave, no LoRC
+}
+
+hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                              Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, void* workspace, hipStream_t s,
+                              const uint16_t* X, int64_t ldx, uint8_t* Xq_out, float* sx_out)
+{
+    const FusedIn fin{X, ldx, Xq_out, sx_out};
     if (L.N == 0) return hipSuccess;
     const int cus = compute_units();
     const bool exact = accum == 0;
@@ -298,14 +371,19 @@ hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, con
     const int64_t per_chunk = L.nstrips < cus / nch ? L.nstrips : cus / nch;
     const unsigned grid = (unsigned)(per_chunk * nch);
     hipError_t e;
-    if (len <= 8) e = launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 16) e = launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 24) e = launch_kpw<8, 3, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 32) e = launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 40) e = launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 48) e = launch_kpw<8, 6, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else if (len <= 56) e = launch_kpw<8, 7, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
-    else e = launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, s);
+    // 16 waves (four per SIMD) where a wave then owns at most two k-tiles: more loads in flight per compute unit
+    if (g_decode_waves.load(std::memory_order_relaxed) == 16 && len <= 32) {
+        if (len <= 16) e = launch_kpw<16, 1, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+        else e = launch_kpw<16, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    } else
+    if (len <= 8) e = launch_kpw<8, 1, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 16) e = launch_kpw<8, 2, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 24) e = launch_kpw<8, 3, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 32) e = launch_kpw<8, 4, 4>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 40) e = launch_kpw<8, 5, 3>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 48) e = launch_kpw<8, 6, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else if (len <= 56) e = launch_kpw<8, 7, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
+    else e = launch_kpw<8, 8, 2>(grid, exact, Xq, sx, m, blob, L, lk, Y, ldy, out_dtype, nch, len, partial, fin, s);
     if (e != hipSuccess || nch == 1) return e;
     return launch_splitk_reduce(partial, nch, M, blob, L, sx, lorc, Y, ldy, out_dtype, s);
 }

@@ -17,40 +17,6 @@ namespace {
 
 constexpr int kRegChunks = 4;  // 16-byte chunks per thread kept in registers
 
-__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-__device__ inline uint32_t absmax_bits(uint32_t acc, uint4 v)
-{
-    // |bf16| ordering equals the ordering of the 15 magnitude bits
-    uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-        acc = max(acc, max(lo, hi));
-    }
-    return acc;
-}
-
-__device__ inline float clamp448(float y) { return fminf(fmaxf(y, -448.0f), 448.0f); }
-
-// 8 bf16 -> 8 E4M3 codes (two dwords)
-__device__ inline uint2 encode8(uint4 v, float inv)
-{
-    uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    float y[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        y[2 * i] = clamp448(bf16_lo(w[i]) * inv);
-        y[2 * i + 1] = clamp448(bf16_hi(w[i]) * inv);
-    }
-    int p0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
-    p0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], p0, true);
-    int p1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], 0, false);
-    p1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], p1, true);
-    return make_uint2((uint32_t)p0, (uint32_t)p1);
-}
-
 __device__ inline float half_bits_to_float(uint32_t h) { return half_bits_to_f32((uint16_t)h); }
 
 // acc[j] += sum_i x_i * U[k_i][j] for the 8 elements (x_i, k_i = kbase + 64 i) that a lane picked up

@@ -263,6 +263,35 @@ int zqfp_w4a8_gemm_lorc_static(const uint8_t* Xq, const float* sx, int64_t M, in
                        stream);
 }
 
+int zqfp_w4a8_linear(const void* X, int64_t ldx, int64_t M, int64_t K, const void* packed, int64_t N, int G, const void* U,
+                     const void* V, int r, uint8_t* Xq, float* sx, float* T, void* Y, int64_t ldy, int out_dtype, int accum,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N < 0 || r < 0 || r > 64) return ZQFP_E_SHAPE;
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L) || ldx < K) return ZQFP_E_SHAPE;
+    if (out_dtype != ZQFP_OUT_F32 && out_dtype != ZQFP_OUT_BF16) return ZQFP_E_MODE;
+    if (accum != ZQFP_ACCUM_EXACT && accum != ZQFP_ACCUM_FAST) return ZQFP_E_MODE;
+    if (M == 0 || N == 0) return ZQFP_OK;
+    if (zqfp::gemm_decode_fused_supported(M, L, r)) {
+        // one kernel: the decode GEMM quantizes the tokens in its prologue
+        if (!X || !packed || !Y) return ZQFP_E_NULL;
+        if (ldy < N) return ZQFP_E_SHAPE;
+        if (!aligned16(X) || (ldx % 8) != 0 || !aligned16(Xq) || !aligned16(Y) ||
+            (reinterpret_cast<uintptr_t>(packed) & 255u) != 0)
+            return ZQFP_E_ALIGN;
+        hipError_t e = zqfp::launch_gemm_decode(nullptr, nullptr, M, static_cast<const uint8_t*>(packed), L,
+                                                zqfp::Lorc{nullptr, nullptr, 0}, Y, ldy, out_dtype, accum, nullptr,
+                                                static_cast<hipStream_t>(stream), u16(X), ldx, Xq, sx);
+        return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+    }
+    // two kernels: the quantizer (with the LoRC left factor), then the GEMM; the intermediate buffers are the caller's
+    if (!Xq || !sx) return ZQFP_E_NULL;
+    const int rc = quantize_common(X, M, K, ldx, Xq, sx, U, r, T, zqfp::Producer{0, nullptr, nullptr, nullptr, 0, nullptr, 0.0f}, stream);
+    if (rc != ZQFP_OK) return rc;
+    return gemm_common(Xq, sx, M, K, packed, N, G, T, V, r, Y, ldy, out_dtype, accum, workspace, workspace_bytes, stream);
+}
+
 size_t zqfp_lorc_workspace_bytes(int64_t K, int64_t N, int r)
 {
     if (K <= 0 || N <= 0 || r < 1 || r > 64) return 0;
@@ -320,6 +349,13 @@ int zqfp_probe_stream_read(const void* src, int64_t bytes, void* sink, int workg
 int zqfp_probe_force_tile_plan(int bm, int bn, int ksplit, int kg)
 {
     return zqfp::force_tile_plan(bm, bn, ksplit, kg) ? ZQFP_OK : ZQFP_E_SHAPE;
+}
+
+int zqfp_probe_force_decode_waves(int nw)
+{
+    if (nw != 8 && nw != 16) return ZQFP_E_SHAPE;
+    zqfp::force_decode_waves(nw);
+    return ZQFP_OK;
 }
 
 int zqfp_probe_mfma(const void* operands, void* sink, int iters, int workgroups, void* stream)

@@ -128,6 +128,57 @@ __device__ inline void split_exponent_bands(const zq_v8i& a, zq_v8i& hi, zq_v8i&
 }
 
 // ---------------------------------------------------------------------------
+// Token-wise E4M3 quantizer arithmetic, shared by the quantizer kernels and the decode GEMM that quantizes in
+// its prologue: the same binary32 sequence everywhere, so that the codes have one right answer.
+// ---------------------------------------------------------------------------
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ inline uint32_t absmax_bits(uint32_t acc, uint4 v)
+{
+    // |bf16| ordering equals the ordering of the 15 magnitude bits
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+        acc = max(acc, max(lo, hi));
+    }
+    return acc;
+}
+
+__device__ inline float clamp448(float y) { return fminf(fmaxf(y, -448.0f), 448.0f); }
+
+// 8 bf16 -> 8 E4M3 codes (two dwords)
+__device__ inline uint2 encode8(uint4 v, float inv)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float y[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        y[2 * i] = clamp448(bf16_lo(w[i]) * inv);
+        y[2 * i + 1] = clamp448(bf16_hi(w[i]) * inv);
+    }
+    int p0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+    p0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], p0, true);
+    int p1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], 0, false);
+    p1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], p1, true);
+    return make_uint2((uint32_t)p0, (uint32_t)p1);
+}
+
+// token scale and its reciprocal from the row's absmax (15 magnitude bits of a bf16): IEEE binary32 divisions;
+// an all-zero (or vanishing, < 2^-96) token gets scale 1 and signed-zero codes
+__device__ inline void token_scale(uint32_t absmax_bf16_bits, float& scale, float& inv)
+{
+    const float amax = __uint_as_float(absmax_bf16_bits << 16);
+    scale = 1.0f;
+    inv = 0.0f;
+    if (amax >= 0x1p-96f) {
+        scale = amax / 448.0f;
+        inv = 448.0f / amax;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // E2M1 and scale helpers shared by the weight-side kernels (packer, GPTQ, LoRC error matrix)
 // ---------------------------------------------------------------------------
 __device__ inline float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -236,9 +287,14 @@ TilePlan effective_tile_plan(int64_t M, int64_t Np, int64_t nkt);
 bool force_tile_plan(int bm, int bn, int ksplit, int kg);
 
 // workspace: plan_decode(nkt).chunks * M * Np floats when K has more than 64 k-tiles (else unused)
+// X != nullptr: the fused form (gemm_decode_fused_supported): bfloat16 activations, quantized in the kernel's
+// prologue; Xq and sx are then unused, Xq_out / sx_out (may be null) receive the codes and scales.
 hipError_t launch_gemm_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
-                              int accum, void* workspace, hipStream_t s);
+                              int accum, void* workspace, hipStream_t s, const uint16_t* X = nullptr,
+                              int64_t ldx = 0, uint8_t* Xq_out = nullptr, float* sx_out = nullptr);
+bool gemm_decode_fused_supported(int64_t M, const BlobLayout& L, int r);
+void force_decode_waves(int nw);  // tuning hook: 8 or 16 waves per workgroup of the decode form
 bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace);
 int compute_units();  // of the current device (asked once)
 // Y[m,n] = (sx[m] c[n]) * sum_s partial[s][m][n] (+ T.V): the second kernel of every K-split

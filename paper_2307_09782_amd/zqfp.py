@@ -61,6 +61,9 @@ def lib():
                                           c.c_size_t, p]
         L.zqfp_w4a8_gemm_lorc_static.restype = c.c_int
         L.zqfp_w4a8_gemm_lorc_static.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p]
+        L.zqfp_w4a8_linear.restype = c.c_int
+        L.zqfp_w4a8_linear.argtypes = [p, i64, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, p, p, p, i64, c.c_int, c.c_int, p,
+                                       c.c_size_t, p]
         L.zqfp_packed_weight_check.restype = c.c_int
         L.zqfp_packed_weight_check.argtypes = [p, i64, i64, c.c_int]
         L.zqfp_rmsnorm_quantize_act_fp8.restype = c.c_int
@@ -87,6 +90,8 @@ def lib():
         L.zqfp_probe_stream_read.argtypes = [p, i64, p, c.c_int, p]
         L.zqfp_probe_force_tile_plan.restype = c.c_int
         L.zqfp_probe_force_tile_plan.argtypes = [c.c_int, c.c_int, c.c_int, c.c_int]
+        L.zqfp_probe_force_decode_waves.restype = c.c_int
+        L.zqfp_probe_force_decode_waves.argtypes = [c.c_int]
         L.zqfp_probe_mfma.restype = c.c_int
         L.zqfp_probe_mfma.argtypes = [p, p, c.c_int, c.c_int, p]
         _lib = L
@@ -360,6 +365,39 @@ def w4a8_gemm_lorc(Xq, sx, packed, N, G, T, V, out_dtype=torch.float32, accum=AC
     return _gemm_call(Xq, sx, packed, N, G, T, V, out_dtype, accum, out, workspace)
 
 
+def linear_is_fused(M, K, r=0):
+    """Whether w4a8_linear runs as one kernel (the decode GEMM quantizing in its prologue)."""
+    return 1 <= M <= 16 and K <= 4096 and r == 0
+
+
+def w4a8_linear(X, packed, N, G, U=None, V=None, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None, want_codes=False):
+    """Y = Q8(X) . Q4(W) (+ (X.U).V) from bfloat16 X in one call (one kernel for at most 16 tokens, K <= 4096 and no
+    LoRC).  Returns Y, or (Y, Xq, sx) with want_codes."""
+    _rows(X, torch.bfloat16), _dev(packed, torch.uint8, 1)
+    M, K = X.shape
+    r = 0
+    if U is not None:
+        _dev(U, torch.float16, 2), _dev(V, torch.float16, 2)
+        r = U.shape[1]
+        if U.shape[0] != K or tuple(V.shape) != (r, N):
+            raise ZqfpError(-2, "LoRC factor shapes")
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
+    check_gemm_args(M, K, N, G, packed.numel(), None, Y.shape, Y.dtype, Y.stride(), Y.is_cuda)
+    fused = linear_is_fused(M, K, r)
+    Xq = sx = T = None
+    if want_codes or not fused:
+        Xq = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+        sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    if r:
+        T = torch.empty((M, r), dtype=torch.float32, device=X.device)
+    ws = None if fused else _workspace(M, K, N, X.device)
+    code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
+    _check(lib().zqfp_w4a8_linear(_ptr(X), X.stride(0), M, K, _ptr(packed), N, G, _ptr(U), _ptr(V), r, _ptr(Xq), _ptr(sx),
+                                  _ptr(T), _ptr(Y), Y.stride(0), code, accum, _ptr(ws), 0 if ws is None else ws.numel(),
+                                  _stream(X)))
+    return (Y, Xq, sx) if want_codes else Y
+
+
 def gptq_pack_weight_fp4(W, Hinv_u, G, mode):
     """GPTQ on the E2M1 grid: W [K,N] bf16, Hinv_u [K,K] f32 (upper Cholesky factor of the inverse Hessian)
     -> the packed blob (same format as pack_weight_fp4)."""
@@ -418,3 +456,8 @@ def probe_force_tile_plan(bm=0, bn=0, ksplit=0, kg=1):
     """Tuning hook: fix tile shape, wave groups and number of K slices of the tiled GEMM for the calls that follow
     (0, 0, 0 = plan automatically again)."""
     _check(lib().zqfp_probe_force_tile_plan(bm, bn, ksplit, kg if bm else 0))
+
+
+def probe_force_decode_waves(nw=8):
+    """Tuning hook: 8 or 16 waves per workgroup of the decode GEMM (K <= 4096)."""
+    _check(lib().zqfp_probe_force_decode_waves(nw))
