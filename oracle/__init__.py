@@ -81,6 +81,11 @@ def lib():
         L.orc_gemm_samples.restype = None
         L.orc_gemm_samples.argtypes = [p, p, c.c_int64, c.c_int64, p, p, p, c.c_int64, c.c_int,
                                        p, p, c.c_int, p, p, c.c_int64, p, p]
+        L.orc_pack_weight_fp8.restype = c.c_int64
+        L.orc_pack_weight_fp8.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, p, p, p, p]
+        L.orc_gemm_w8_samples.restype = None
+        L.orc_gemm_w8_samples.argtypes = [p, p, c.c_int64, c.c_int64, p, p, p, p, c.c_int64, c.c_int, p, p, c.c_int,
+                                          p, p, c.c_int64, p, p]
         L.orc_lorc_left.restype = None
         L.orc_lorc_left.argtypes = [p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int, p, p]
         L.orc_rmsnorm_bf16.restype = None
@@ -212,6 +217,42 @@ def pack_weight(W, G, mode):
     c = np.empty((N,), np.float32)
     clipped = lib().orc_pack_weight(_ptr(W), K, N, N, G, mode, _ptr(codes), _ptr(exps), _ptr(c))
     return codes, exps, c, int(clipped)
+
+
+def pack_weight_fp8(W, G, mode):
+    """E4M3 weights (W8A8).  mode 0 = real group scales (the paper's W8A8 rows), 1 = M1, 2 = M2.
+    Returns codes [K,N] (E4M3), exps [K/G,N], c [N], gscale [K/G,N] (each group's whole scale), saturated count."""
+    _chk(W, np.uint16, 2)
+    K, N = W.shape
+    assert K % G == 0 and mode in (0, 1, 2)
+    codes = np.empty((K, N), np.uint8)
+    exps = np.empty((K // G, N), np.uint8)
+    c = np.empty((N,), np.float32)
+    gscale = np.empty((K // G, N), np.float32)
+    clipped = lib().orc_pack_weight_fp8(_ptr(W), K, N, N, G, mode, _ptr(codes), _ptr(exps), _ptr(c), _ptr(gscale))
+    return codes, exps, c, gscale, int(clipped)
+
+
+def gemm_w8(Xq, sx, codes, exps, c, G, gscale=None, T=None, V=None, ms=None, ns=None):
+    """W8A8 layer: Y (and Sabs) for the sampled outputs (ms, ns), or for the whole [M,N] matrix when none are given.
+    gscale: real group scales (mode 0), else the power-of-two exponents `exps` are used."""
+    _chk(Xq, np.uint8, 2), _chk(sx, np.float32, 1), _chk(codes, np.uint8, 2), _chk(exps, np.uint8, 2), _chk(c, np.float32, 1)
+    M, K = Xq.shape
+    N = codes.shape[1]
+    assert codes.shape[0] == K and exps.shape == (K // G, N)
+    T, V, r = _lorc_args(T, V, M, N)
+    full = ms is None
+    if full:
+        ms, ns = np.divmod(np.arange(M * N, dtype=np.int64), N)
+    ms = np.ascontiguousarray(ms, np.int64)
+    ns = np.ascontiguousarray(ns, np.int64)
+    if gscale is not None:
+        _chk(gscale, np.float32, 2)
+    Y = np.empty(ms.shape, np.float32)
+    Sabs = np.empty(ms.shape, np.float64)
+    lib().orc_gemm_w8_samples(_ptr(Xq), _ptr(sx), M, K, _ptr(codes), _ptr(exps), _ptr(c), _ptr(gscale), N, G,
+                              _ptr(T), _ptr(V), r, _ptr(ms), _ptr(ns), ms.size, _ptr(Y), _ptr(Sabs))
+    return (Y.reshape(M, N), Sabs.reshape(M, N)) if full else (Y, Sabs)
 
 
 def _lorc_args(T, V, M, N):

@@ -548,6 +548,126 @@ void orc_gemm_samples(const uint8_t *Xq, const float *sx, int64_t M, int64_t K,
 }
 
 /* ------------------------------------------------------------------ */
+/* W8A8: FP8 (E4M3) weights against FP8 activations                     */
+/* ------------------------------------------------------------------ */
+
+/* The paper's second weight format (Section 4, Table 2, rows W8A8 / FP -- FP;
+ * "FP8 weights rival INT8"): group-wise E4M3 weights, fine-grained quantization
+ * as for FP4 (Section 3), scale S = amax / 448 (the format's largest value in
+ * place of E2M1's 6).
+ *   mode 0: S_g real (what the paper's W8A8 rows use): S_g = fl32(amax_g / 448),
+ *           y = fl32(w / S_g); gscale[g][n] = S_g (1 for a zero group), exps = 127,
+ *           colscale = 1.
+ *   mode 1: (M1) S^_g = 2^n, least n with amax_g <= 448 * 2^n; y = w * 2^-n (exact).
+ *   mode 2: (M2) c[n] = fl32(amax_max / 448), S^_g = c[n] * 2^-k with the same k as
+ *           for FP4 (the format's largest value cancels in S_max / S_g);
+ *           y = fl32(w / c[n]) * 2^k; values beyond 448 saturate.
+ * codes: K x N E4M3 codes.  exps: (K/G) x N bytes (n + 127, or 127 - k).
+ * gscale: (K/G) x N floats, written in every mode (2^n, c 2^-k: the group's whole
+ * scale), may be NULL.  Returns the number of saturated elements. */
+static int m1_exponent_fmax(double amax, double fmax)
+{
+    int n = 0;
+    if (amax == 0.0)
+        return 0;
+    while (amax > ldexp(fmax, n))
+        ++n;
+    while (amax <= ldexp(fmax, n - 1))
+        --n;
+    if (n < -126) n = -126;
+    if (n > 127) n = 127;
+    return n;
+}
+
+int64_t orc_pack_weight_fp8(const uint16_t *W, int64_t K, int64_t N, int64_t ldw,
+                            int G, int mode, uint8_t *codes, uint8_t *exps,
+                            float *colscale, float *gscale)
+{
+    int64_t ng = K / G, clipped = 0;
+    double *amax = (double *)malloc((size_t)ng * sizeof(double));
+    for (int64_t n = 0; n < N; ++n) {
+        double amax_max = 0.0;
+        for (int64_t g = 0; g < ng; ++g) {
+            double a = 0.0;
+            for (int64_t k = g * G; k < (g + 1) * G; ++k) {
+                double v = fabs((double)bf16_bits_to_f32(W[k * ldw + n]));
+                if (v > a)
+                    a = v;
+            }
+            amax[g] = a;
+            if (a > amax_max)
+                amax_max = a;
+        }
+        volatile float c = 1.0f;
+        if (mode == 2 && amax_max > 0.0)
+            c = (float)amax_max / 448.0f; /* one binary32 division */
+        colscale[n] = c;
+        for (int64_t g = 0; g < ng; ++g) {
+            int e = 0;        /* exponent of the power of two in the group's scale */
+            volatile float s = 1.0f; /* the real part of the group's scale */
+            if (mode == 0) {
+                if (amax[g] > 0.0)
+                    s = (float)amax[g] / 448.0f;
+            } else if (mode == 1) {
+                e = m1_exponent_fmax(amax[g], 448.0);
+            } else {
+                e = -m2_shift(amax_max, amax[g]);
+                s = c;
+            }
+            exps[g * N + n] = (uint8_t)(e + 127);
+            if (gscale)
+                gscale[g * N + n] = (float)ldexp((double)s, e);
+            for (int64_t k = g * G; k < (g + 1) * G; ++k) {
+                float w = bf16_bits_to_f32(W[k * ldw + n]);
+                volatile float q = (mode == 1) ? w : w / s; /* binary32 division (none under M1) */
+                double y = ldexp((double)q, -e);               /* exact */
+                if (fabs(y) > 448.0)
+                    ++clipped;
+                /* |y| <= 448 * 2 at most, far inside binary32: the conversion is exact */
+                codes[k * N + n] = orc_e4m3_encode((float)y);
+            }
+        }
+    }
+    free(amax);
+    return clipped;
+}
+
+/* acc[m][n] = sum_k dec8(Xq[m][k]) * dec8(codes[k][n]) * scale(k/G, n), in k order in fp64, where the
+ * group's scale is 2^(exps-127) (modes 1, 2; gscale == NULL) or gscale[g][n] (mode 0);
+ * Y = fl32( fl32(sx[m] * colscale[n]) * acc )  (+ T.V as in orc_gemm).  One output at a time: for the
+ * full matrix pass every (m, n). */
+void orc_gemm_w8_samples(const uint8_t *Xq, const float *sx, int64_t M, int64_t K,
+                         const uint8_t *codes, const uint8_t *exps, const float *colscale,
+                         const float *gscale, int64_t N, int G, const float *T,
+                         const uint16_t *V, int r, const int64_t *ms, const int64_t *ns,
+                         int64_t count, float *Y, double *Sabs)
+{
+    (void)M;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t m = ms[i], n = ns[i];
+        double acc = 0.0, aab = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double sc = gscale ? (double)gscale[(k / G) * N + n]
+                               : ldexp(1.0, (int)exps[(k / G) * N + n] - 127);
+            double p = orc_e4m3_decode(Xq[m * K + k]) * (orc_e4m3_decode(codes[k * N + n]) * sc);
+            acc += p;
+            aab += fabs(p);
+        }
+        volatile float sc = sx[m] * colscale[n];
+        double y = (double)sc * acc, ya = fabs((double)sc) * aab;
+        for (int j = 0; j < r; ++j) {
+            double tv = (double)T[m * r + j] * fp16_bits_to_f64(V[(int64_t)j * N + n]);
+            y += tv;
+            ya += fabs(tv);
+        }
+        Y[i] = (float)y;
+        if (Sabs)
+            Sabs[i] = ya;
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* LoRC left factor (Section 3): T = X . U from the un-quantized X      */
 /* ------------------------------------------------------------------ */
 
