@@ -366,6 +366,48 @@ int zqfp_w4a8_gemm_lorc(const uint8_t *Xq, const float *sx, int64_t M, int64_t K
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * W8A8: FP8 (E4M3) weights against FP8 activations (paper Section 4, Table 2,
+ * rows "W8A8 ... FP -- FP"; "FP8 weights rival INT8").  Group-wise weight
+ * scales as for FP4 (Section 3) with the format's largest value 448 in place
+ * of 6, constrained to powers of two by the same two methods (M1: per group
+ * 2^ceil(log2(amax_g / 448)); M2: c[n] * 2^-k_g), so that the matrix
+ * instruction's block exponent applies them.  Real-valued group scales (what the
+ * paper's W8A8 rows use) would need a multiply per group and output in the
+ * accumulation loop and are not offered.
+ *
+ * pack_weight_fp8 / unpack_codes_fp8 / packed_weight_fp8_bytes mirror the FP4
+ * calls (codes are E4M3 bytes; G must be a multiple of 128).  The blob's header
+ * records the code width; zqfp_packed_weight_check accepts both kinds.
+ *
+ * w8a8_gemm:  Y[m,n] = (sx[m] c[n]) * sum_k v(Xq[m,k]) v(q[k,n]) 2^n_g  (+ T.V).
+ * Arguments as for zqfp_w4a8_gemm_lorc (T = V = NULL, r = 0: no LoRC); no
+ * workspace.  Accumulation: an FP8 x FP8 product has up to 8 significant bits, so
+ * inside the matrix core's 13-bit window of a run of 8 consecutive k only
+ * products within 7 binades of the run's largest are summed exactly; neither
+ * mode can promise the W4A8 bound (16 passes over 4 x 4 exponent bands would).
+ * Worst case for both modes: |err| <= 7 * 2^-13 * sum_k |a_k w_k| (the seven
+ * smaller products of a run each lose less than 2^-13 of the largest one).
+ * ZQFP_ACCUM_EXACT here means two passes over the activation's exponent bands,
+ * as for W4A8: it removes the part of the truncation that comes from the
+ * activations' dynamic range (outlier channels), not the part that comes from
+ * the weights' own spread inside a run.  Measured on the benchmark
+ * distributions: relative Frobenius error 2..3 * 10^-5 and |err| <= 10^-5 *
+ * sum|a w| with two passes, 3..6 * 10^-5 and 1.6 * 10^-5 with one
+ * (ZQFP_ACCUM_FAST); truncation is toward zero, so the error is a small bias
+ * toward smaller magnitudes rather than noise.
+ */
+size_t zqfp_packed_weight_fp8_bytes(int64_t K, int64_t N, int G);
+int zqfp_pack_weight_fp8(const void *W, int64_t K, int64_t N, int64_t ldw,
+                         int G, int mode, void *packed, void *stream);
+int zqfp_unpack_codes_fp8(const void *packed, int64_t K, int64_t N, int G,
+                          uint8_t *codes, uint8_t *exps, float *colscale,
+                          void *stream);
+int zqfp_w8a8_gemm(const uint8_t *Xq, const float *sx, int64_t M, int64_t K,
+                   const void *packed, int64_t N, int G,
+                   const float *T, const void *V, int r,
+                   void *Y, int64_t ldy, int out_dtype, int accum, void *stream);
+
+/*
  * w4a8_linear -- the whole layer in one call, from bfloat16 activations:
  * zqfp_quantize_act_fp8 followed by zqfp_w4a8_gemm(_lorc) (paper Section 3:
  * token-wise activation quantization is chosen for latency; for a handful of

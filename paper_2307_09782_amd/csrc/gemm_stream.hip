@@ -26,7 +26,9 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kUnroll = 4;  // k-tiles whose loads are issued before their matrix instructions
 
-template <int MT, bool EXACT>
+// W8: the weights are E4M3 codes (W8A8, paper Section 4): a fragment is two 1 KB halves, the B operand has eight
+// registers and the instruction's format field says FP8 on both sides.
+template <int MT, bool EXACT, bool W8 = false>
 __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restrict__ Xq, const float* __restrict__ sx,
                                                         int64_t M, const uint8_t* __restrict__ blob, BlobLayout L,
                                                         Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype)
@@ -38,7 +40,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
     const int64_t m_base = (int64_t)blockIdx.y * (16 * MT);
     const int nkt = (int)L.nkt;
 
-    const u32x4* bfrag = reinterpret_cast<const u32x4*>(blob + L.off_codes) + strip * nkt * 64 + lane;
+    constexpr int kFragVec = W8 ? 128 : 64;  // 16-byte vectors per fragment
+    const u32x4* bfrag = reinterpret_cast<const u32x4*>(blob + L.off_codes) + strip * nkt * kFragVec + lane;
     const uint32_t* ex = reinterpret_cast<const uint32_t*>(blob + L.off_exps) + strip * L.ngq * 16 + col;
 
     // A operand of the instruction: lane (row = lane%16, lb = lane/16) holds the bytes
@@ -57,14 +60,15 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
     for (int t = 0; t < MT; ++t) acc[t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     for (int kt0 = wave; kt0 < nkt; kt0 += kWaves * kUnroll) {
-        u32x4 b[kUnroll];
+        u32x4 b[kUnroll], b2[W8 ? kUnroll : 1];
         uint32_t e[kUnroll];
         u32x4 a_lo[kUnroll][MT], a_hi[kUnroll][MT];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int kt = kt0 + u * kWaves;
             if (kt < nkt) {
-                b[u] = bfrag[(int64_t)kt * 64];
+                b[u] = bfrag[(int64_t)kt * kFragVec];
+                if constexpr (W8) b2[u] = bfrag[(int64_t)kt * kFragVec + 64];
                 const int blk = kt * 4 + lb;  // 32-element block index along K
                 const int sg = (L.gsb_shift >= 0) ? (blk >> L.gsb_shift) : (blk / L.gsb);
                 e[u] = ex[(sg >> 2) * 16] >> (8 * (sg & 3));
@@ -85,6 +89,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
             const int kt = kt0 + u * kWaves;
             if (kt < nkt) {
                 v8i bv = {(int)b[u][0], (int)b[u][1], (int)b[u][2], (int)b[u][3], 0, 0, 0, 0};
+                if constexpr (W8) { bv[4] = (int)b2[u][0]; bv[5] = (int)b2[u][1]; bv[6] = (int)b2[u][2]; bv[7] = (int)b2[u][3]; }
+                constexpr int kBlgp = W8 ? 0 : 4;  // format of B: 0 = E4M3, 4 = E2M1
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
                     v8i av = {(int)a_lo[u][t][0], (int)a_lo[u][t][1], (int)a_lo[u][t][2], (int)a_lo[u][t][3],
@@ -93,10 +99,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm_stream(const uint8_t* __restr
                     if constexpr (EXACT) {
                         v8i hi, lo;
                         split_exponent_bands(av, hi, lo);
-                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc[t], 0, 4, 0, 127, 0, (int)e[u]);
-                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lo, bv, acc[t], 0, 4, 0, 127, 0, (int)e[u]);
+                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc[t], 0, kBlgp, 0, 127, 0, (int)e[u]);
+                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lo, bv, acc[t], 0, kBlgp, 0, 127, 0, (int)e[u]);
                     } else {
-                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[t], 0, 4, 0, 127, 0, (int)e[u]);
+                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[t], 0, kBlgp, 0, 127, 0, (int)e[u]);
                     }
                 }
             }
@@ -131,10 +137,10 @@ template <int MT>
 void launch_mt(dim3 grid, bool exact, const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, hipStream_t s)
 {
-    if (exact)
-        hipLaunchKernelGGL((k_gemm_stream<MT, true>), grid, dim3(kThreads), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
-    else
-        hipLaunchKernelGGL((k_gemm_stream<MT, false>), grid, dim3(kThreads), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype);
+#define ZQ_STREAM(EX, W8) hipLaunchKernelGGL((k_gemm_stream<MT, EX, W8>), grid, dim3(kThreads), 0, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype)
+    if (L.wbits == 8) { if (exact) ZQ_STREAM(true, true); else ZQ_STREAM(false, true); }
+    else { if (exact) ZQ_STREAM(true, false); else ZQ_STREAM(false, false); }
+#undef ZQ_STREAM
 }
 
 }  // namespace

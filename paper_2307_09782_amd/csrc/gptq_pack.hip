@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void k_gptq_init(const uint16_t* __restrict__ 
         BlobHeader h;
         h.magic = kBlobMagic; h.version = kBlobVersion;
         h.K = L.K; h.N = L.N; h.Np = L.Np;
-        h.G = L.G; h.Gs = L.Gs; h.mode = mode; h.ngs = L.ngs; h.ngq = L.ngq; h.pad_ = 0;
+        h.G = L.G; h.Gs = L.Gs; h.mode = mode; h.ngs = L.ngs; h.ngq = L.ngq; h.wbits = 4;
         h.off_codes = L.off_codes; h.off_exps = L.off_exps; h.off_colscale = L.off_colscale; h.total = L.total;
         *reinterpret_cast<BlobHeader*>(blob) = h;
     }

@@ -49,11 +49,12 @@ __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __rest
     if (tid < 16) {
         float cs = 1.0f;
         if (mode == 1) {
-            for (int g = 0; g < ng; ++g) s_ebyte[g * 16 + tid] = m1_exponent(s_gmax[g * 16 + tid]) + 127;
+            for (int g = 0; g < ng; ++g)
+                s_ebyte[g * 16 + tid] = (L.wbits == 8 ? m1_exponent_e4m3(s_gmax[g * 16 + tid]) : m1_exponent(s_gmax[g * 16 + tid])) + 127;
         } else {
             float mx = 0.0f;
             for (int g = 0; g < ng; ++g) mx = fmaxf(mx, s_gmax[g * 16 + tid]);
-            if (mx != 0.0f) cs = mx / 6.0f;  // IEEE binary32 division
+            if (mx != 0.0f) cs = mx / (L.wbits == 8 ? 448.0f : 6.0f);  // IEEE binary32 division
             for (int g = 0; g < ng; ++g) s_ebyte[g * 16 + tid] = 127 - m2_shift(mx, s_gmax[g * 16 + tid]);
         }
         s_col[tid] = cs;
@@ -73,6 +74,44 @@ __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __rest
             word |= e << (8 * b);
         }
         reinterpret_cast<uint32_t*>(blob + L.off_exps)[(size_t)strip * L.ngq * 16 + i] = word;
+    }
+
+    if (L.wbits == 8) {
+        // phase 3, E4M3 codes: fragment = [half][64 lanes][4 dwords]; a dword holds 4 consecutive k.  Same encoder
+        // as the activations': clamp to +-448, then the hardware conversion (round to nearest even, sign kept).
+        uint32_t* out8 = reinterpret_cast<uint32_t*>(blob + L.off_codes) + (size_t)strip * L.nkt * 512;
+        for (int64_t kt = 0; kt < L.nkt; ++kt) {
+            for (int idx = tid; idx < 512; idx += kThreads) {
+                const int half = idx >> 8, ln = (idx >> 2) & 63, dd = idx & 3;
+                const int cc = ln & 15, lbb = ln >> 4;
+                const int64_t nn = (int64_t)strip * 16 + cc;
+                const int64_t k0 = kt * 128 + 64 * half + 16 * lbb + 4 * dd;
+                const int e = s_ebyte[(int)(k0 / L.G) * 16 + cc] - 127;
+                const float csn = s_col[cc];
+                uint32_t word = 0;
+                if (nn < L.N) {
+                    float y[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float w = bf16_bits_to_f32(W[(k0 + i) * ldw + nn]);
+                        y[i] = clamp448((mode == 1) ? ldexpf(w, -e) : ldexpf(w / csn, -e));
+                    }
+                    int pk = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+                    pk = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], pk, true);
+                    word = (uint32_t)pk;
+                }
+                out8[kt * 512 + idx] = word;
+            }
+        }
+        if (strip == 0 && tid == 0) {
+            BlobHeader h;
+            h.magic = kBlobMagic; h.version = kBlobVersion;
+            h.K = L.K; h.N = L.N; h.Np = L.Np;
+            h.G = L.G; h.Gs = L.Gs; h.mode = mode; h.ngs = L.ngs; h.ngq = L.ngq; h.wbits = 8;
+            h.off_codes = L.off_codes; h.off_exps = L.off_exps; h.off_colscale = L.off_colscale; h.total = L.total;
+            *reinterpret_cast<BlobHeader*>(blob) = h;
+        }
+        return;
     }
 
     // phase 3: codes, one dword (8 codes) per thread per fragment
@@ -102,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void k_pack_weight(const uint16_t* __rest
         BlobHeader h;
         h.magic = kBlobMagic; h.version = kBlobVersion;
         h.K = L.K; h.N = L.N; h.Np = L.Np;
-        h.G = L.G; h.Gs = L.Gs; h.mode = mode; h.ngs = L.ngs; h.ngq = L.ngq; h.pad_ = 0;
+        h.G = L.G; h.Gs = L.Gs; h.mode = mode; h.ngs = L.ngs; h.ngq = L.ngq; h.wbits = 4;
         h.off_codes = L.off_codes; h.off_exps = L.off_exps; h.off_colscale = L.off_colscale; h.total = L.total;
         *reinterpret_cast<BlobHeader*>(blob) = h;
     }
@@ -118,8 +157,13 @@ __global__ __launch_bounds__(kThreads) void k_unpack(const uint8_t* __restrict__
         const int64_t k = i / L.N, n = i % L.N;
         const int64_t strip = n >> 4, kt = k >> 7;
         const int c = (int)(n & 15), kk = (int)(k & 127), lb = kk >> 5, p = kk & 31;
-        const uint8_t byte = blob[L.off_codes + ((size_t)(strip * L.nkt + kt) * 64 + (lb * 16 + c)) * 16 + (p >> 1)];
-        codes[i] = (p & 1) ? (byte >> 4) : (byte & 15);
+        if (L.wbits == 8) {
+            const int half = kk >> 6, lb8 = (kk >> 4) & 3;
+            codes[i] = blob[L.off_codes + (size_t)(strip * L.nkt + kt) * 2048 + half * 1024 + (lb8 * 16 + c) * 16 + (kk & 15)];
+        } else {
+            const uint8_t byte = blob[L.off_codes + ((size_t)(strip * L.nkt + kt) * 64 + (lb * 16 + c)) * 16 + (p >> 1)];
+            codes[i] = (p & 1) ? (byte >> 4) : (byte & 15);
+        }
     }
     const int64_t ng = L.K / L.G;
     if (i < ng * L.N) {

@@ -200,15 +200,67 @@ int zqfp_pack_weight_fp4(const void* W, int64_t K, int64_t N, int64_t ldw, int G
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 
+size_t zqfp_packed_weight_fp8_bytes(int64_t K, int64_t N, int G)
+{
+    zqfp::BlobLayout L;
+    return zqfp::make_layout(K, N, G, &L, 8) ? L.total : 0;
+}
+
+int zqfp_pack_weight_fp8(const void* W, int64_t K, int64_t N, int64_t ldw, int G, int mode, void* packed, void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L, 8) || ldw < N) return ZQFP_E_SHAPE;
+    if (mode != ZQFP_SCALE_M1 && mode != ZQFP_SCALE_M2) return ZQFP_E_MODE;
+    if (!packed || (N > 0 && !W)) return ZQFP_E_NULL;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return ZQFP_E_ALIGN;
+    if (N == 0) return ZQFP_OK;
+    hipError_t e = zqfp::launch_pack_weight(static_cast<const uint16_t*>(W), ldw, L, mode, static_cast<uint8_t*>(packed),
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_unpack_codes_fp8(const void* packed, int64_t K, int64_t N, int G, uint8_t* codes, uint8_t* exps, float* colscale,
+                          void* stream)
+{
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L, 8)) return ZQFP_E_SHAPE;
+    if (N == 0) return ZQFP_OK;
+    if (!packed || !codes || !exps || !colscale) return ZQFP_E_NULL;
+    hipError_t e = zqfp::launch_unpack(static_cast<const uint8_t*>(packed), L, codes, exps, colscale,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
+int zqfp_w8a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, const void* packed, int64_t N, int G,
+                   const float* T, const void* V, int r, void* Y, int64_t ldy, int out_dtype, int accum, void* stream)
+{
+    if (M < 0 || N < 0 || r < 0 || r > 64) return ZQFP_E_SHAPE;
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L, 8)) return ZQFP_E_SHAPE;
+    if (out_dtype != ZQFP_OUT_F32 && out_dtype != ZQFP_OUT_BF16) return ZQFP_E_MODE;
+    if (accum != ZQFP_ACCUM_EXACT && accum != ZQFP_ACCUM_FAST) return ZQFP_E_MODE;
+    if (M == 0 || N == 0) return ZQFP_OK;
+    if (!Xq || !sx || !packed || !Y) return ZQFP_E_NULL;
+    if (r > 0 && (!T || !V)) return ZQFP_E_NULL;
+    if (ldy < N) return ZQFP_E_SHAPE;
+    if (!aligned16(Xq) || !aligned16(Y) || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return ZQFP_E_ALIGN;
+    zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* blob = static_cast<const uint8_t*>(packed);
+    hipError_t e = M <= 64 ? zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                           : zqfp::launch_gemm_w8_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
+    return e == hipSuccess ? ZQFP_OK : hip_fail(e);
+}
+
 int zqfp_packed_weight_check(const void* header, int64_t K, int64_t N, int G)
 {
     static_assert(sizeof(zqfp::BlobHeader) <= ZQFP_BLOB_HEADER_BYTES, "header size");
     if (!header) return ZQFP_E_NULL;
-    zqfp::BlobLayout L;
-    if (!zqfp::make_layout(K, N, G, &L)) return ZQFP_E_SHAPE;
     zqfp::BlobHeader h;
     std::memcpy(&h, header, sizeof h);
-    const bool ok = h.magic == zqfp::kBlobMagic && h.version == zqfp::kBlobVersion && h.K == L.K && h.N == L.N &&
+    zqfp::BlobLayout L;
+    if (!zqfp::make_layout(K, N, G, &L, h.wbits == 8 ? 8 : 4)) return ZQFP_E_SHAPE;
+    const bool ok = (h.wbits == 4 || h.wbits == 8) && h.magic == zqfp::kBlobMagic && h.version == zqfp::kBlobVersion && h.K == L.K && h.N == L.N &&
                     h.Np == L.Np && h.G == L.G && h.Gs == L.Gs && h.ngs == L.ngs && h.ngq == L.ngq &&
                     (h.mode == ZQFP_SCALE_M1 || h.mode == ZQFP_SCALE_M2) && h.off_codes == L.off_codes &&
                     h.off_exps == L.off_exps && h.off_colscale == L.off_colscale && h.total == L.total;

@@ -49,7 +49,7 @@ struct BlobHeader {
     uint32_t version;  // layout version
     int64_t K, N, Np;
     int32_t G, Gs, mode, ngs, ngq;
-    uint32_t pad_;
+    uint32_t wbits;    // 4: E2M1 codes, 8: E4M3 codes
     uint64_t off_codes, off_exps, off_colscale, total;
 };
 constexpr uint32_t kBlobMagic = 0x3446515Au;  // "ZQF4"
@@ -58,6 +58,9 @@ constexpr uint32_t kBlobVersion = 1;
 struct BlobLayout {
     int64_t K, N, Np, nstrips, nkt;
     int G, Gs, ngs, ngq;
+    int wbits;      // weight code width: 4 (E2M1) or 8 (E4M3: fragments of 2 KB, [half][64 lanes][16 B], where half h
+                    // of lane l holds k = 128*ktile + 64*h + 16*(l/16) + [0,16) -- the FP8 operand order of the
+                    // matrix instruction, each half one contiguous 1 KB read)
     int gsb;        // 32-element blocks per stored group (Gs / 32)
     int gsb_shift;  // log2(gsb) if gsb is a power of two, else -1
     uint32_t gq_magic;  // groups of >= 128: stored group of k-tile kt is (kt * gq_magic) >> 20 (exact for kt < 16384)
@@ -67,9 +70,12 @@ struct BlobLayout {
 inline int gcd_int(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
 
 // Returns false if (K, N, G) violates the documented shape limits.
-inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
+inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L, int wbits = 4)
 {
     if (K <= 0 || N < 0 || G <= 0 || K % 128 != 0 || G % 32 != 0 || K % G != 0) return false;
+    if (wbits != 4 && wbits != 8) return false;
+    if (wbits == 8 && G % 128 != 0) return false;  // E4M3 weights: one exponent byte per k-tile and column
+    L->wbits = wbits;
     if (K / G > 256) return false;
     if (K / 128 >= 4096) return false;  // the k-tile -> group division by multiplication (gq_magic) is exact below this
     L->K = K; L->N = N; L->Np = (N + 15) / 16 * 16;
@@ -84,7 +90,7 @@ inline bool make_layout(int64_t K, int64_t N, int G, BlobLayout* L)
         L->gq_magic = (uint32_t)(((1 << 20) + gq - 1) / gq);  // gq <= 64, so kt * gq_magic < 2^32 for kt < 4096
     }
     L->off_codes = 256;
-    L->off_exps = L->off_codes + (size_t)L->Np * (size_t)K / 2;
+    L->off_exps = L->off_codes + (size_t)L->Np * (size_t)K * (size_t)wbits / 8;
     size_t exps_bytes = (size_t)L->nstrips * L->ngq * 64;
     L->off_colscale = (L->off_exps + exps_bytes + 255) / 256 * 256;
     L->total = (L->off_colscale + (size_t)L->Np * 4 + 255) / 256 * 256;
@@ -195,6 +201,18 @@ __device__ inline int m1_exponent(float amax)
     return min(127, max(-126, n));
 }
 
+// the same for E4M3 weights: least integer n with amax <= 448 * 2^n (448 = 1.75 * 2^8)
+__device__ inline int m1_exponent_e4m3(float amax)
+{
+    if (amax == 0.0f) return 0;
+    const uint32_t b = __float_as_uint(amax);
+    const int ex = (int)(b >> 23);
+    if (ex == 0) return -126;
+    const uint32_t man = b & 0x7FFFFFu;
+    const int n = (ex - 127) - ((man <= 0x600000u) ? 8 : 7);  // significand <= 1.75 ?
+    return min(127, max(-126, n));
+}
+
 // least k >= 0 with amax_max <= amax_g * 2^k (= ceil(log2(S_max / S_g))), clamped to 15
 __device__ inline int m2_shift(float amax_max, float amax_g)
 {
@@ -276,6 +294,10 @@ hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* code
 hipError_t launch_gemm_stream(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                               int accum, hipStream_t s);
+// W8A8 (E4M3 weights, L.wbits == 8), more than 64 tokens: 128 x 128 tiles through LDS
+hipError_t launch_gemm_w8_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
+                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
+                               int accum, hipStream_t s);
 // workspace: device memory of plan_tiles(...).ksplit * M * Np floats, or nullptr (then K is not split)
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                             const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,

@@ -64,6 +64,14 @@ def lib():
         L.zqfp_w4a8_linear.restype = c.c_int
         L.zqfp_w4a8_linear.argtypes = [p, i64, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, p, p, p, i64, c.c_int, c.c_int, p,
                                        c.c_size_t, p]
+        L.zqfp_packed_weight_fp8_bytes.restype = c.c_size_t
+        L.zqfp_packed_weight_fp8_bytes.argtypes = [i64, i64, c.c_int]
+        L.zqfp_pack_weight_fp8.restype = c.c_int
+        L.zqfp_pack_weight_fp8.argtypes = [p, i64, i64, i64, c.c_int, c.c_int, p, p]
+        L.zqfp_unpack_codes_fp8.restype = c.c_int
+        L.zqfp_unpack_codes_fp8.argtypes = [p, i64, i64, c.c_int, p, p, p, p]
+        L.zqfp_w8a8_gemm.restype = c.c_int
+        L.zqfp_w8a8_gemm.argtypes = [p, p, i64, i64, p, i64, c.c_int, p, p, c.c_int, p, i64, c.c_int, c.c_int, p]
         L.zqfp_packed_weight_check.restype = c.c_int
         L.zqfp_packed_weight_check.argtypes = [p, i64, i64, c.c_int]
         L.zqfp_rmsnorm_quantize_act_fp8.restype = c.c_int
@@ -396,6 +404,51 @@ def w4a8_linear(X, packed, N, G, U=None, V=None, out_dtype=torch.float32, accum=
                                   _ptr(T), _ptr(Y), Y.stride(0), code, accum, _ptr(ws), 0 if ws is None else ws.numel(),
                                   _stream(X)))
     return (Y, Xq, sx) if want_codes else Y
+
+
+def pack_weight_fp8(W, G, mode):
+    """W [K,N] bf16 -> packed blob of E4M3 weights with power-of-two group scales (W8A8; G a multiple of 128)."""
+    _rows(W, torch.bfloat16)
+    K, N = W.shape
+    nbytes = int(lib().zqfp_packed_weight_fp8_bytes(K, N, G))
+    if nbytes == 0:
+        raise ZqfpError(-2, f"(K={K}, N={N}, G={G})")
+    packed = torch.empty((nbytes,), dtype=torch.uint8, device=W.device)
+    _check(lib().zqfp_pack_weight_fp8(_ptr(W), K, N, W.stride(0), G, mode, _ptr(packed), _stream(W)))
+    return packed
+
+
+def unpack_codes_fp8(packed, K, N, G):
+    """packed E4M3 blob -> codes [K,N] uint8 (E4M3), exps [K/G,N] uint8, colscale [N] f32."""
+    _dev(packed, torch.uint8, 1)
+    if packed.numel() != int(lib().zqfp_packed_weight_fp8_bytes(K, N, G)) or packed.numel() == 0:
+        raise ZqfpError(-2, "blob size is not that of an E4M3 blob of (K, N, G)")
+    codes = torch.empty((K, N), dtype=torch.uint8, device=packed.device)
+    exps = torch.empty((K // G, N), dtype=torch.uint8, device=packed.device)
+    colscale = torch.empty((N,), dtype=torch.float32, device=packed.device)
+    _check(lib().zqfp_unpack_codes_fp8(_ptr(packed), K, N, G, _ptr(codes), _ptr(exps), _ptr(colscale), _stream(packed)))
+    return codes, exps, colscale
+
+
+def w8a8_gemm(Xq, sx, packed, N, G, T=None, V=None, out_dtype=torch.float32, accum=ACCUM_EXACT, out=None):
+    """Y [M,N] = (sx c) * (Xq . Wq8) (+ T . V): E4M3 weights."""
+    _dev(Xq, torch.uint8, 2), _dev(sx, torch.float32, 1), _dev(packed, torch.uint8, 1)
+    M, K = Xq.shape
+    if packed.numel() != int(lib().zqfp_packed_weight_fp8_bytes(K, N, G)) or packed.numel() == 0 or sx.shape[0] != M:
+        raise ZqfpError(-2, "blob size is not that of an E4M3 blob of (K, N, G)")
+    r = 0
+    if T is not None:
+        _dev(T, torch.float32, 2), _dev(V, torch.float16, 2)
+        r = T.shape[1]
+        if T.shape[0] != M or tuple(V.shape) != (r, N):
+            raise ZqfpError(-2, "LoRC factor shapes")
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    if Y.dtype not in (torch.float32, torch.bfloat16) or tuple(Y.shape) != (M, N) or not Y.is_cuda or (N > 1 and Y.stride(1) != 1):
+        raise ZqfpError(-2, "output must be a CUDA [M, N] float32 / bfloat16 tensor with contiguous rows")
+    code = OUT_F32 if Y.dtype == torch.float32 else OUT_BF16
+    _check(lib().zqfp_w8a8_gemm(_ptr(Xq), _ptr(sx), M, K, _ptr(packed), N, G, _ptr(T), _ptr(V), r, _ptr(Y), Y.stride(0),
+                                code, accum, _stream(Xq)))
+    return Y
 
 
 def gptq_pack_weight_fp4(W, Hinv_u, G, mode):

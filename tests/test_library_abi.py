@@ -94,7 +94,7 @@ def test_argument_checks_return_error_codes_without_a_gpu(lib):
 
 
 def test_packed_weight_check_reads_a_host_copy_of_the_header(lib):
-    """Header fields as the packer writes them (magic 'ZQF4', version, K, N, Np, G, Gs, mode, ngs, ngq, pad,
+    """Header fields as the packer writes them (magic 'ZQF4', version, K, N, Np, G, Gs, mode, ngs, ngq, code width,
     four section offsets): accepted for its own (K, N, G), refused for any other and after any damage."""
     import struct
     K, N, G = 512, 200, 64
@@ -106,14 +106,14 @@ def test_packed_weight_check_reads_a_host_copy_of_the_header(lib):
     ngq = (ngs + 3) // 4
     off_cs = (off_exps + (Np // 16) * ngq * 64 + 255) // 256 * 256
     assert total == (off_cs + 4 * Np + 255) // 256 * 256
-    hdr = struct.pack("<IIqqqiiiiiIQQQQ", 0x3446515A, 1, K, N, Np, G, 64, 2, ngs, ngq, 0, off_codes, off_exps, off_cs, total)
+    hdr = struct.pack("<IIqqqiiiiiIQQQQ", 0x3446515A, 1, K, N, Np, G, 64, 2, ngs, ngq, 4, off_codes, off_exps, off_cs, total)
     hdr = hdr + bytes(256 - len(hdr))
     chk = lambda h, k, n, g: lib.zqfp_packed_weight_check(h, k, n, g)
     assert chk(hdr, K, N, G) == 0
     assert chk(hdr, K, N, 128) == -7 and chk(hdr, K, N + 1, G) == -7 and chk(hdr, 2 * K, N, G) == -7
     assert chk(hdr, K, N, 48) == -2 and chk(None, K, N, G) == -1
     assert chk(b"\0" * 256, K, N, G) == -7
-    for pos in (0, 4, 8, 16, 32, 40, 56, 80):
+    for pos in (0, 4, 8, 16, 32, 40, 52, 56, 80):
         bad = bytearray(hdr)
         bad[pos] ^= 1
         assert chk(bytes(bad), K, N, G) == -7, pos
