@@ -412,3 +412,33 @@ def gptq_fp4(W, Hinv_u, G, mode):
         if k + 1 < K:
             Wf[k + 1:] -= np.outer(Hinv_u[k, k + 1:], err)
     return codes, exps, c, Q
+
+
+# ---- format ablation helpers (Appendix A, Table A.1: E2M1 against E3M0 weights; Section 4: E4M3 against E5M2) ----
+def format_values(name):
+    """Non-negative values of a small floating-point format, ascending, index = magnitude code.
+    e2m1, e4m3, e5m2: decoded by the C oracle.  e3m0: sign, three exponent bits (bias 3), no mantissa bit --
+    0, then 2^(E - 3) for E = 1..7 (the paper's alternative 4-bit format; it names the format only, the bias is
+    immaterial under an absmax scale)."""
+    if name == "e2m1":
+        return np.array([e2m1_decode(q) for q in range(8)])
+    if name == "e3m0":
+        return np.array([0.0] + [2.0 ** (e - 3) for e in range(1, 8)])
+    if name == "e4m3":
+        return np.array([e4m3_decode(q) for q in range(0x7F)])          # 0x7F is NaN
+    if name == "e5m2":
+        return np.array([e5m2_decode(q) for q in range(0x7C)])          # 0x7C.. are infinity / NaN
+    raise ValueError(name)
+
+
+def quantize_to_format(y, name):
+    """Nearest value of the format for every element of y (ties to the even magnitude code, saturating at the
+    largest value, sign kept): the definition written out over the value table.  Returns the values (float64)."""
+    tab = format_values(name)
+    y = np.asarray(y, np.float64)
+    a = np.minimum(np.abs(y), tab[-1])
+    hi = np.clip(np.searchsorted(tab, a, side="left"), 1, len(tab) - 1)
+    lo = hi - 1
+    dl, dh = a - tab[lo], tab[hi] - a
+    pick_hi = (dh < dl) | ((dh == dl) & (hi % 2 == 0))
+    return np.copysign(np.where(pick_hi, tab[hi], tab[lo]), y)
