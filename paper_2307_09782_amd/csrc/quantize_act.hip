@@ -17,6 +17,8 @@ namespace {
 
 constexpr int kRegChunks = 4;  // 16-byte chunks per thread kept in registers
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
 __device__ inline float half_bits_to_float(uint32_t h) { return half_bits_to_f32((uint16_t)h); }
 
 // acc[j] += sum_i x_i * U[k_i][j] for the 8 elements (x_i, k_i = kbase + 64 i) that a lane picked up
@@ -397,8 +399,13 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
     const uint16_t* __restrict__ bias = pr.bias;
     const float eps = pr.eps;
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= M) return;  // whole waves leave; nothing below synchronises across waves
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    bool live = true;  // LORC: the four waves stage U together, so a wave past the last token stays, repeats that token and stores nothing
+    if (row >= M) {
+        if constexpr (!LORC) return;  // whole waves leave; nothing below synchronises across waves
+        live = false;
+        row = M - 1;
+    }
     const uint4* xrow = reinterpret_cast<const uint4*>(X + row * ldx);
     uint2* qrow = reinterpret_cast<uint2*>(Xq + row * K);
     const int nchunk = (int)(K / 8);
@@ -420,10 +427,10 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
                 if (idx < nchunk) {
                     if constexpr (NORM == 4) {
                         v[c] = swiglu8(v[c], orow[idx]);
-                        if (pr.H != nullptr) hrow[idx] = v[c];
+                        if (pr.H != nullptr && live) hrow[idx] = v[c];
                     } else {
                         v[c] = add8(v[c], orow[idx]);
-                        hrow[idx] = v[c];
+                        if (live) hrow[idx] = v[c];
                     }
                 }
             }
@@ -459,31 +466,53 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
         }
     }
     float acc[8];
-    if constexpr (LORC) {  // first, so that the loads of U are in flight during the absmax reduction
+    if constexpr (LORC) {
         // A lane holds 8 consecutive elements; it trades them, through the wave's own 1 KB of LDS, for elements
-        // lane, lane + 64, ... of the chunk's 512, so that one load instruction of the wave covers 64
-        // consecutive rows of U (1 KB contiguous) instead of 64 separate lines.
+        // lane, lane + 64, ... of the chunk's 512, so that lane l meets rows l, l + 64, ... of U.  The 512 rows of U
+        // that a chunk needs (8 KB) are staged in LDS once per workgroup and serve its four tokens: every token
+        // re-reading U from L2 made the call twice as slow as the plain quantizer at 2048 tokens.  Two buffers, so one
+        // barrier per chunk: chunk c + 1 is fetched into the other buffer while chunk c is multiplied.
         __shared__ __attribute__((aligned(16))) uint16_t s_x[4][512];
+        __shared__ __attribute__((aligned(16))) uint4 s_u[2][512];
         const int wave = threadIdx.x >> 6;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
         const uint4* u4 = reinterpret_cast<const uint4*>(U);  // row k of U (8 binary16 values) is u4[k]
+        auto fetch_u = [&](int c, uint4& a, uint4& b) {  // rows wave * 128 + lane and + 64 of chunk c (past K: the last row; x is zero there)
+            const int64_t k0 = (int64_t)c * 512 + wave * 128 + lane;
+            a = u4[k0 < K ? k0 : K - 1];
+            b = u4[k0 + 64 < K ? k0 + 64 : K - 1];
+        };
+        uint4 ua, ub;
+        fetch_u(0, ua, ub);
+        s_u[0][wave * 128 + lane] = ua;
+        s_u[0][wave * 128 + 64 + lane] = ub;
+        __syncthreads();
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
-            if (c * 64 < nchunk) {  // the same for the whole wave
+            if (c * 64 < nchunk) {  // the same for the whole workgroup
+                const bool more = (c + 1) * 64 < nchunk;
+                if (more) fetch_u(c + 1, ua, ub);
                 *reinterpret_cast<uint4*>(&s_x[wave][lane * 8]) = v[c];  // same wave writes and reads: no barrier
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float x = __uint_as_float((uint32_t)s_x[wave][lane + 64 * i] << 16);
-                    const int64_t k = (int64_t)c * 512 + 64 * i + lane;
-                    const uint4 u = u4[k < K ? k : K - 1];  // past the row's end x is zero
+                    const uint4 u = s_u[c & 1][64 * i + lane];
                     const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        acc[2 * q] = fmaf(x, half_bits_to_float(uw[q] & 0xFFFFu), acc[2 * q]);
-                        acc[2 * q + 1] = fmaf(x, half_bits_to_float(uw[q] >> 16), acc[2 * q + 1]);
+                        // binary16 halves of a dword, widened inside the multiply-add (mixed-precision FMA: the same
+                        // exact widening and one binary32 rounding as convert-then-fma, without the conversions)
+                        const half2_t p = __builtin_bit_cast(half2_t, uw[q]);
+                        acc[2 * q] = fmaf(x, (float)p[0], acc[2 * q]);
+                        acc[2 * q + 1] = fmaf(x, (float)p[1], acc[2 * q + 1]);
                     }
                 }
+                if (more) {  // the other buffer's readers (chunk c - 1) passed the previous barrier
+                    s_u[(c + 1) & 1][wave * 128 + lane] = ua;
+                    s_u[(c + 1) & 1][wave * 128 + 64 + lane] = ub;
+                }
+                __syncthreads();
             }
         }
     }
@@ -498,11 +527,11 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
         scale = amax / 448.0f;  // IEEE binary32 division
         inv = 448.0f / amax;    // IEEE binary32 division
     }
-    if (lane == 0) sx[row] = scale;
+    if (lane == 0 && live) sx[row] = scale;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int idx = c * 64 + lane;
-        if (idx < nchunk) qrow[idx] = encode8(v[c], inv);
+        if (idx < nchunk && live) qrow[idx] = encode8(v[c], inv);
     }
     if constexpr (LORC) {
 #pragma unroll
@@ -510,7 +539,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
             float a = acc[j];
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off);
-            if (lane == 0) T[row * 8 + j] = a;
+            if (lane == 0 && live) T[row * 8 + j] = a;
         }
     }
 }
@@ -522,9 +551,10 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
 {
     if (M == 0) return hipSuccess;
     const int kind = pr.kind;
-    // many tokens, no LoRC factor: one wave per token; so too with the rank-8 factor on rows of more than 4096
-    // elements (measured: 6-10 % faster there, slower on shorter rows)
-    if (M >= 1024 && K <= 8192 && (r == 0 || (r == 8 && K > 4096))) {
+    // many tokens: one wave per token, without the LoRC factor or with the rank-8 one (its four waves share U through
+    // LDS; 4096 x 4096 with the factor: 25.3 -> 21.5 us against the workgroup-per-token kernel, 4096 x 2048: 19.1 -> 12.9).
+    // With the factor the call is bound by issuing the K x 8 multiply-adds per token, not by memory.
+    if (M >= 1024 && K <= 8192 && (r == 0 || r == 8)) {
         const dim3 g4((unsigned)((M + 3) / 4));
 #define ZQ_ROWS_N(MAXC, KIND)                                                                                               \
     do {                                                                                                                    \
