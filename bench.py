@@ -383,6 +383,8 @@ def main():
     ap.add_argument("--accum", choices=["exact", "fast"], default="exact")
     ap.add_argument("--no-also", action="store_true", help="skip the extra shapes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--only-quantizer", action="store_true",
+                    help="run the quantizer rows alone and print them (for profiling the quantizer kernels)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (yardstick for rocprofv3 HBM byte counters)")
     args = ap.parse_args()
@@ -395,6 +397,9 @@ def main():
 
     if args.calib_copy:
         calibration_copy()
+    if args.only_quantizer:
+        print(json.dumps({"quantizer": quantizer_rows()}), flush=True)
+        return
     decode = args.M <= 64
     copies = 1
     if decode:  # HBM-bound: rotate through weight copies that together exceed the 256 MB last-level cache
