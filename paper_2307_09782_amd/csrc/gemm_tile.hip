@@ -185,19 +185,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     const uint8_t* b_base = blob + L.off_codes;               // uniform
     const uint8_t* e_base = blob + L.off_exps;                // uniform
     const int rows_here = (int)min((int64_t)C::BM, M - m0);   // >= 1
-    uint32_t a_off[C::A_CHUNKS], b_off[C::B_CHUNKS];
+    uint32_t a_off[C::A_CHUNKS];
 #pragma unroll
     for (int i = 0; i < C::A_CHUNKS; ++i) {
         const int row = (wave + (kGT / 64) * i) * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ (row & 7);
         a_off[i] = (uint32_t)(min(row, rows_here - 1) * (int)L.K + 16 * chunk);
     }
+    // a wave's i-th weight load is one whole strip (1 KB per k-tile): which strip is the same for all its lanes, so
+    // it travels in the scalar base address and the lanes share one offset register
+    const uint32_t b_lane = (uint32_t)lane * 16u;
+    int64_t b_strip[C::B_CHUNKS];  // byte offset of the strip's first k-tile (wave-uniform)
 #pragma unroll
-    for (int i = 0; i < C::B_CHUNKS; ++i) {
-        const int cidx = tid + kGT * i;
-        const int64_t strip = min(strip0 + (cidx >> 6), L.nstrips - 1);
-        b_off[i] = (uint32_t)((strip * nkt_all * 64 + (cidx & 63)) * 16);
-    }
+    for (int i = 0; i < C::B_CHUNKS; ++i)
+        b_strip[i] = min(strip0 + wave + (kGT / 64) * i, L.nstrips - 1) * nkt_all * 1024;
     // exponent dwords, [strip][quad][column] in memory: thread t stages the dword of column
     // t % BN of the tile; it lands in LDS as [column] and every lane later picks its own.
     const uint32_t e_off = 4u * ((uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15));
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         const uint32_t st = (uint32_t)stage * C::STAGE;
         if (t < C::A_CHUNKS) lds_load16(a_base + (kt0 + KG * kt) * 128, a_off[t], st + a_dst + t * (kGT / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            lds_load16(b_base + (int64_t)(kt0 + KG * kt) * 1024, b_off[t - C::A_CHUNKS], st + b_dst + (t - C::A_CHUNKS) * (kGT / 64) * 1024);
+            lds_load16(b_base + b_strip[t - C::A_CHUNKS] + (int64_t)(kt0 + KG * kt) * 1024, b_lane, st + b_dst + (t - C::A_CHUNKS) * (kGT / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
             lds_load4(e_base + __builtin_amdgcn_readfirstlane((group_of(c, kt0 + KG * kt, 0) >> 2) * 64), e_off, st + e_dst);
     };
@@ -266,17 +267,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     auto as_v8i = [](const u32x4& p, const u32x4& q) {
         return (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
     };
-    // The band split of the shared header in four operations instead of five for the small wave tiles: the two
-    // constants of the byte selector live in registers (one scalar, one vector), so that "and" and "or" are one
-    // three-operand instruction.  Plain vector operations take matrix-pipe time (about 3.5 cycles each beyond
-    // three per matrix instruction, measured on register-only loops), and with few column blocks per wave the
-    // split is most of them.  The large wave tiles have no register to spare and stay below that threshold anyway.
-    constexpr bool kSplit4 = WTM * WTN <= 16;
+    // The band split of the shared header in four operations instead of five: the two constants of the byte
+    // selector live in registers (one scalar, one vector), so that "and" and "or" are one three-operand
+    // instruction.  Plain vector operations take matrix-pipe time (about 3.5 cycles each beyond three per matrix
+    // instruction, measured on register-only loops), and the split is most of them.
+    constexpr bool kSplit4 = true;
     uint32_t k_sel_base = 0x03020100u, k_sel_mask = 0x04040404u;
-    if constexpr (kSplit4) {
-        asm volatile("" : "+v"(k_sel_base));  // opaque: keeps the constants in registers
-        asm volatile("" : "+s"(k_sel_mask));
-    }
+    asm volatile("" : "+v"(k_sel_base));  // opaque: keeps the constants in registers
+    asm volatile("" : "+s"(k_sel_mask));
     auto split_in_place = [&](v8i& frag, int d) __attribute__((always_inline)) {  // dword d of frag -> upper band into fx, lower band stays
         const uint32_t x = (uint32_t)frag[d];
         uint32_t h, l;
