@@ -9,6 +9,8 @@ import os
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
+from . import check_lds_waits
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
@@ -31,6 +33,9 @@ def sources():
 # between such a read and its wait would save a value that has not arrived yet, so these must
 # compile without scratch memory.  The compiler's resource remarks are checked after every build.
 NO_SCRATCH_KERNELS = ("k_gemm_tile",)
+# The same kernels' device assembly is kept by the compile and checked for another thing the compiler may do to
+# such reads: copy their destination register before the wait (see check_lds_waits).
+HAND_WAIT_SOURCES = {"gemm_tile.hip": "k_gemm_tile"}
 
 
 def _run(cmd):
@@ -61,11 +66,16 @@ def build_lib(verbose=False, jobs=8):
     os.makedirs(OBJDIR, exist_ok=True)
     srcs = sources()
     objs = [os.path.join(OBJDIR, os.path.basename(s)[:-4] + ".o") for s in srcs]
-    cmds = [[HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", s, "-o", o] for s, o in zip(srcs, objs)]
+    cmds = [[HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage",
+             *(["-save-temps=obj"] if os.path.basename(s) in HAND_WAIT_SOURCES else []), "-c", s, "-o", o] for s, o in zip(srcs, objs)]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         outs = list(ex.map(_run, cmds))
     for o in outs:
         _check_no_scratch(o)
+    for src, kernel in HAND_WAIT_SOURCES.items():
+        listing = os.path.join(OBJDIR, src[:-4] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        with open(listing) as f:
+            check_lds_waits.check_text(f.read(), kernel)
     outs = ["\n".join(l for l in o.splitlines() if "kernel-resource-usage" not in l and not l.lstrip().startswith(("|", "^")) and not l.strip().split(" ", 1)[0].isdigit()) for o in outs]
     outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
     if verbose:

@@ -393,10 +393,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         }
     });
     if (nkt >= NSTAGE) advance(cur_load);
-    // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done (waiting for
-    // more than necessary is always safe: loads complete in order)
+    // k-tile 0 has landed, for every wave, once all but the later tiles' loads are done.  A pipeline shorter than
+    // the stages waits for everything here, so that the first step's barrier below needs no second form: the code
+    // behind this point has LDS reads in flight, and a branch with two copies of it invites the register
+    // allocator to copy a fragment register between its read and its wait (the build checks the listing for that).
     if (nkt >= NSTAGE) wait_loads_then_barrier<(NSTAGE - 1) * NSIDE>();
-    else if (nkt > 1) wait_loads_then_barrier<NSIDE>();
     else wait_loads_then_barrier<0>();
     ta = lds_read16<0>(a_addr0);
     tb = lds_read16<0>(a_addr1);
@@ -423,8 +424,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     using W1 = std::integral_constant<int, (NSTAGE - 2) * NSIDE>;
     using W0 = std::integral_constant<int, 0>;
     int stage = 0;
-    if (nkt >= NSTAGE) head_blocks(0, 0, W1{});  // k-tiles 2 .. NSTAGE - 1 may still be on their way
-    else head_blocks(0, 0, W0{});
+    head_blocks(0, 0, W1{});  // k-tiles 2 .. NSTAGE - 1 may still be on their way (a shorter pipeline has nothing outstanding)
     int kt = 0;
     for (; kt + NSTAGE < nkt; ++kt) {  // k-tile kt + NSTAGE exists
         row_block(std::integral_constant<int, WTM - 1>{}, kt, stage_off(stage), stage_off(next(stage)), stage, yes{}, yes{});
