@@ -24,6 +24,10 @@
 // chunks (whole cache lines on the way in, conflict-free 16 B/lane operand
 // reads on the way out); the weight tile already has its operand order in
 // memory and is copied as is.
+//
+// The same kernel serves FP8 (E4M3) weights, the W8A8 rows of the paper's Table 2 with FP8 on both sides
+// (template parameter WB = 8): a strip's k-tile is then two 1 KB halves, the first and the second four
+// registers of the B operand, the operand takes two LDS reads, and the instruction is told that B is E4M3.
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
@@ -82,6 +86,16 @@ __device__ inline void wait_lds(u32x4& a, uint32_t& b, u32x4& c, u32x4& d)
 {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
+template <int N>
+__device__ inline void wait_lds(u32x4& a, uint32_t& b, u32x4& c)
+{
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(N));
+}
+template <int N>
+__device__ inline void wait_lds(u32x4& a, uint32_t& b, u32x4& c, u32x4& d, u32x4& e)
+{
+    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e) : "n"(N));
+}
 template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F&& f)
 {
@@ -102,13 +116,15 @@ __device__ inline void wait_loads_then_barrier()
 // kt % KG), each with its own operands in LDS and its own accumulators; the groups' sums meet in LDS in the
 // epilogue.  KG = 2 gives the small tile two waves per SIMD where the tile count leaves one workgroup per
 // compute unit.  GT = threads of one group; the per-group quantities below are written in terms of it.
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE_, int KG_ = 1>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE_, int KG_ = 1, int WB = 4>
 struct TileCfg {
+    static_assert(WB == 4 || WB == 8, "weight bits: E2M1 or E4M3");
     static constexpr int KG = KG_;
+    static constexpr int B_STRIP = 256 * WB;  // bytes of one strip (16 output channels) of one k-tile
     static constexpr int GT = 64 * WAVES_M * WAVES_N;
     static constexpr int THREADS = GT * KG;
     static constexpr int BM = WAVES_M * WTM * 16, BN = WAVES_N * WTN * 16;
-    static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 64;
+    static constexpr int A_BYTES = BM * 128, B_BYTES = BN / 16 * B_STRIP;
     static constexpr int E_BYTES = GT * 4;                    // one exponent dword per output channel (first BN used)
     static constexpr int SUB = A_BYTES + B_BYTES + E_BYTES;   // one k-tile's operands
     static constexpr int STAGE = SUB * KG;
@@ -125,13 +141,14 @@ struct TileCfg {
 
 // Two waves per SIMD in every configuration (8-wave workgroups alone on a compute unit, 4-wave
 // workgroups in pairs): 256 registers per lane.
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT, int WB = 4>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_tile(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int64_t M, const uint8_t* __restrict__ blob,
     BlobLayout L, Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int tiles_m, int tiles_n, int ksplit,
     int kslice, float* __restrict__ partial)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, WB>;
+    static_assert(WB == 4 || WTN == 4, "E4M3 weights: three LDS reads per column block, and the counter of outstanding reads holds 15");
     constexpr int kThreads = C::THREADS;  // of the workgroup
     constexpr int kGT = C::GT;            // of one wave group
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -195,10 +212,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     // a wave's i-th weight load is one whole strip (1 KB per k-tile): which strip is the same for all its lanes, so
     // it travels in the scalar base address and the lanes share one offset register
     const uint32_t b_lane = (uint32_t)lane * 16u;
-    int64_t b_strip[C::B_CHUNKS];  // byte offset of the strip's first k-tile (wave-uniform)
+    int64_t b_strip[C::B_CHUNKS];  // byte offset of the strip's first k-tile (wave-uniform); E4M3: of one 1 KB half of it
 #pragma unroll
-    for (int i = 0; i < C::B_CHUNKS; ++i)
-        b_strip[i] = min(strip0 + wave + (kGT / 64) * i, L.nstrips - 1) * nkt_all * 1024;
+    for (int i = 0; i < C::B_CHUNKS; ++i) {
+        const int q = wave + (kGT / 64) * i;  // 1 KB block q of the tile's weights
+        const int strip = WB == 8 ? q >> 1 : q, half = WB == 8 ? q & 1 : 0;
+        b_strip[i] = min(strip0 + strip, L.nstrips - 1) * nkt_all * C::B_STRIP + half * 1024;
+    }
     // exponent dwords, [strip][quad][column] in memory: thread t stages the dword of column
     // t % BN of the tile; it lands in LDS as [column] and every lane later picks its own.
     const uint32_t e_off = 4u * ((uint32_t)(min(strip0 + ((tid % C::BN) >> 4), L.nstrips - 1) * L.ngq * 16) + (tid & 15));
@@ -235,7 +255,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         const uint32_t st = (uint32_t)stage * C::STAGE;
         if (t < C::A_CHUNKS) lds_load16(a_base + (kt0 + KG * kt) * 128, a_off[t], st + a_dst + t * (kGT / 64) * 1024);
         else if (t < C::A_CHUNKS + C::B_CHUNKS)
-            lds_load16(b_base + b_strip[t - C::A_CHUNKS] + (int64_t)(kt0 + KG * kt) * 1024, b_lane, st + b_dst + (t - C::A_CHUNKS) * (kGT / 64) * 1024);
+            lds_load16(b_base + b_strip[t - C::A_CHUNKS] + (int64_t)(kt0 + KG * kt) * C::B_STRIP, b_lane, st + b_dst + (t - C::A_CHUNKS) * (kGT / 64) * 1024);
         else  // the dword holds 4 stored groups; the four 32-blocks of a k-tile always share one dword
             lds_load4(e_base + __builtin_amdgcn_readfirstlane((group_of(c, kt0 + KG * kt, 0) >> 2) * 64), e_off, st + e_dst);
     };
@@ -255,6 +275,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     // dword per matrix instruction of the lower-band pass, into fx (whose old content the
     // upper-band pass has already consumed) and itself.
     u32x4 bq[WTN];        // weight fragments
+    u32x4 bqh[WTN];       // E4M3 weights: their second halves
     uint32_t e_cur[WTN];  // their exponent dwords (raw until the first use in a step)
     v8i fx, fy, fz;
     u32x4 ta, tb;         // the activation fragment in flight
@@ -262,7 +283,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     // per-lane LDS addresses inside stage 0 (the stage offset is added per step)
     const uint32_t a_addr0 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7)) * 16);
     const uint32_t a_addr1 = lds0 + (wm * WTM) * 2048 + col * 128 + ((lb ^ (col & 7) ^ 4) * 16);
-    const uint32_t b_addr = lds0 + C::A_BYTES + (wn * WTN) * 1024 + lane * 16;
+    const uint32_t b_addr = lds0 + C::A_BYTES + (wn * WTN) * C::B_STRIP + lane * 16;
     const uint32_t e_addr = lds0 + C::A_BYTES + C::B_BYTES + (wn * WTN * 16 + col) * 4;
     auto as_v8i = [](const u32x4& p, const u32x4& q) {
         return (v8i){(int)p[0], (int)p[1], (int)p[2], (int)p[3], (int)q[0], (int)q[1], (int)q[2], (int)q[3]};
@@ -290,6 +311,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
         frag[d] = (int)l;
     };
     constexpr int PASSES = EXACT ? 2 : 1;
+    constexpr int RB = WB == 8 ? 3 : 2;  // LDS reads per column block: exponent dword, weight fragment (two halves if E4M3)
     static_assert(WTM % 2 == 0 && WTN >= 4 && WTN <= 8, "fragment rotation, split slots and wait schedule assume these");
 
     // ---- one row block of a k-step: WTN (x2 in the exact mode) matrix instructions on row block I
@@ -302,8 +324,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     //   * last block only (it runs behind the step's barrier, see below): one per instruction, the
     //     requests for k-tile kt + NSTAGE into this step's stage (LOAD) and, behind the last instruction
     //     that reads them, the next step's weight fragments and exponent dwords (NEXT);
-    //   * block 0: instruction j waits for its own fragment j only (read_b order: e0 b0 e1 b1 ...):
-    //     2 (WTN - 1 - j) younger reads, plus the 2 of the activation request once that is out.
+    //   * block 0: instruction j waits for its own fragment j only (read_b order: e0 b0 e1 b1 ...; E4M3
+    //     weights: e0 b0 b0' e1 ...): RB (WTN - 1 - j) younger reads, RB = 2 or 3 per column block, plus the
+    //     2 of the activation request once that is out.
     auto row_block = [&](auto i_tag, int kt, uint32_t st, uint32_t st_next, int stage, auto load_tag, auto next_tag) __attribute__((always_inline)) {
         constexpr int I = decltype(i_tag)::value;
         constexpr bool LOAD = decltype(load_tag)::value;
@@ -319,12 +342,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
             static_for<0, WTN>([&](auto j_tag) __attribute__((always_inline)) {
                 constexpr int J = decltype(j_tag)::value;
                 if constexpr (I == 0 && P == 0) {
-                    constexpr int YOUNGER = 2 * (WTN - 1 - J) + (J >= 2 ? 2 : 0);
+                    constexpr int YOUNGER = RB * (WTN - 1 - J) + (J >= 2 ? 2 : 0);
                     if constexpr (J == 0 && !EXACT) {  // the fragment that arrived during the previous block
-                        wait_lds<YOUNGER>(bq[J], e_cur[J], ta, tb);
+                        if constexpr (WB == 8) wait_lds<YOUNGER>(bq[J], e_cur[J], bqh[J], ta, tb);
+                        else wait_lds<YOUNGER>(bq[J], e_cur[J], ta, tb);
                         cur = as_v8i(ta, tb);
                     } else {
-                        wait_lds<YOUNGER>(bq[J], e_cur[J]);
+                        if constexpr (WB == 8) wait_lds<YOUNGER>(bq[J], e_cur[J], bqh[J]);
+                        else wait_lds<YOUNGER>(bq[J], e_cur[J]);
                     }
                     e_cur[J] >>= esh;
                 } else if constexpr (I > 0 && P == 0 && J == 0 && !EXACT) {
@@ -336,9 +361,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
                     inc = as_v8i(ta, tb);
                 }
                 const v8i& op = (EXACT && P == 0) ? fx : cur;
-                const v8i bv = {(int)bq[J][0], (int)bq[J][1], (int)bq[J][2], (int)bq[J][3], 0, 0, 0, 0};
-                // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
-                acc[I][J] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bv, acc[I][J], 0, 4, 0, 127, 0, (int)e_cur[J]);
+                // cbsz 0: A is E4M3; blgp 4: B is E2M1 (blgp 0: E4M3); A scale byte 127 = 2^0; B scale = group exponent
+                if constexpr (WB == 8) {
+                    const v8i bv = {(int)bq[J][0], (int)bq[J][1], (int)bq[J][2], (int)bq[J][3], (int)bqh[J][0], (int)bqh[J][1], (int)bqh[J][2], (int)bqh[J][3]};
+                    acc[I][J] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bv, acc[I][J], 0, 0, 0, 127, 0, (int)e_cur[J]);
+                } else {
+                    const v8i bv = {(int)bq[J][0], (int)bq[J][1], (int)bq[J][2], (int)bq[J][3], 0, 0, 0, 0};
+                    acc[I][J] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(op, bv, acc[I][J], 0, 4, 0, 127, 0, (int)e_cur[J]);
+                }
                 if constexpr (P == 0 && J == 1 && fetch) {
                     if constexpr (!last_block) {
                         ta = lds_read16<(I + 1) * 2048>(a_addr0 + st);
@@ -360,7 +390,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
                         if (LOAD && T * PER + q < NSIDE) side_load(T * PER + q, kt + NSTAGE, stage, cur_load);
                     if constexpr (NEXT && P == PASSES - 1) {
                         e_cur[J] = lds_read4<J * 64>(e_addr + st_next);
-                        bq[J] = lds_read16<J * 1024>(b_addr + st_next);
+                        bq[J] = lds_read16<J * C::B_STRIP>(b_addr + st_next);
+                        if constexpr (WB == 8) bqh[J] = lds_read16<J * C::B_STRIP + 1024>(b_addr + st_next);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -404,10 +435,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) __attribute__((amdgpu_
     static_for<0, WTN>([&](auto j_tag) __attribute__((always_inline)) {
         constexpr int J = decltype(j_tag)::value;
         e_cur[J] = lds_read4<J * 64>(e_addr);
-        bq[J] = lds_read16<J * 1024>(b_addr);
+        bq[J] = lds_read16<J * C::B_STRIP>(b_addr);
+        if constexpr (WB == 8) bqh[J] = lds_read16<J * C::B_STRIP + 1024>(b_addr);
     });
     if constexpr (EXACT) {  // the fast mode picks ta, tb up at its first matrix instruction
-        wait_lds<(2 * WTN < 15 ? 2 * WTN : 15)>(ta, tb);  // the counter holds 15 at most
+        wait_lds<(RB * WTN < 15 ? RB * WTN : 15)>(ta, tb);  // the counter holds 15 at most
         fy = as_v8i(ta, tb);
 #pragma unroll
         for (int d = 0; d < 8; ++d) split_in_place(fy, d);
@@ -605,16 +637,16 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 }
 
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int NSTAGE, int KG, bool EXACT, int WB = 4>
 hipError_t launch_cfg(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
                       void* Y, int64_t ldy, int out_dtype, int ksplit, int kslice, float* partial, hipStream_t s)
 {
-    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG>;
+    using C = TileCfg<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, WB>;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (int)((L.Np + C::BN - 1) / C::BN);
     const int units = tiles_m * tiles_n * ksplit;
     const int per = (units + 7) / 8;
     const size_t smem = C::NSTAGE * C::STAGE;
-    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, EXACT>;
+    auto kern = k_gemm_tile<WTM, WTN, WAVES_M, WAVES_N, NSTAGE, KG, EXACT, WB>;
     static OnceStatus attr;  // raising the dynamic LDS limit is a per-function, per-process setting (one flag per instantiation)
     if (hipError_t e = run_once(attr, [&] {
             return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -657,6 +689,27 @@ hipError_t launch_pick(const uint8_t* Xq, const float* sx, int64_t M, const uint
     if (two_groups) ZQ_TILE(2, 4, 2, 2, 3, 2);
     ZQ_TILE(2, 4, 2, 2, 3, 1);
 #undef ZQ_TILE
+}
+
+// E4M3 weights: 128 x 128 tiles, two workgroups per compute unit, once there is more than one of them per compute
+// unit; below that 64 x 128 tiles, with two wave groups while at most one workgroup per compute unit is left (and
+// the k-tiles can be dealt out in pairs).  No K-split: the W8A8 entry point takes no workspace.
+template <bool EXACT>
+hipError_t launch_pick_w8(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L, Lorc lorc,
+                          void* Y, int64_t ldy, int out_dtype, hipStream_t s)
+{
+    auto tiles = [&](int bm) { return ((M + bm - 1) / bm) * ((L.Np + 127) / 128); };
+    int bm = tiles(128) > 256 ? 128 : 64;
+    int kg = bm == 64 && tiles(64) <= 256 ? 2 : 1;
+    const TilePlan f = effective_tile_plan(M, L.Np, L.nkt);
+    if (f.forced && f.bn == 128 && (f.bm == 64 || f.bm == 128)) { bm = f.bm; kg = f.bm == 64 ? f.kg : 1; }
+    if (L.nkt & 1) kg = 1;
+#define ZQ_TILE8(WTM, NST, KG) \
+    return launch_cfg<WTM, 4, 2, 2, NST, KG, EXACT, 8>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, 1, (int)L.nkt, nullptr, s)
+    if (bm == 128) ZQ_TILE8(4, 2, 1);
+    if (kg == 2) ZQ_TILE8(2, 3, 2);
+    ZQ_TILE8(2, 3, 1);
+#undef ZQ_TILE8
 }
 
 std::atomic<uint32_t> g_forced_plan{0};  // bm | bn << 10 | ksplit << 20 | kg << 28; 0 = automatic
@@ -754,6 +807,14 @@ TilePlan effective_tile_plan(int64_t M, int64_t Np, int64_t nkt)
     p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
     p.forced = true;
     return p;
+}
+
+hipError_t launch_gemm_w8_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                               Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
+{
+    if (M == 0 || L.N == 0) return hipSuccess;
+    return accum == 0 ? launch_pick_w8<true>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s)
+                      : launch_pick_w8<false>(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, s);
 }
 
 hipError_t launch_gemm_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,

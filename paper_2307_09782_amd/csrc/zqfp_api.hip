@@ -247,8 +247,9 @@ int zqfp_w8a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, con
     zqfp::Lorc lorc{r > 0 ? T : nullptr, r > 0 ? static_cast<const uint16_t*>(V) : nullptr, r};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* blob = static_cast<const uint8_t*>(packed);
-    hipError_t e = M <= 64 ? zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
-                           : zqfp::launch_gemm_w8_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
+    hipError_t e = M <= 64 || !zqfp::gemm_tile_supported(M, L)
+                       ? zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                       : zqfp::launch_gemm_w8_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);
 }
 

@@ -747,3 +747,19 @@ def test_gemm_every_tile_shape_with_and_without_a_k_split(bm, bn, kg):
         _check_bf16(Y, Y_o, Sabs, f"{bm}x{bn} bf16")
     finally:
         zqfp.probe_force_tile_plan(0, 0, 0)
+
+
+@pytest.mark.parametrize("bm,bn,kg", [(64, 128, 1), (64, 128, 2), (64, 192, 1), (64, 192, 2), (64, 256, 1), (64, 256, 2),
+                                      (128, 128, 1), (128, 192, 1), (128, 256, 1), (256, 256, 1)])
+def test_gemm_every_tile_shape_on_pipelines_shorter_than_the_stages(bm, bn, kg):
+    """Four k-tiles in all, cut so that a wave group multiplies four, two or a single one: fewer than the LDS
+    stages it keeps in flight (two or three), the case in which the pipeline's first step is also its last."""
+    M, K, N, G, mode, r = 300, 512, 1000, 128, 1, 0
+    try:
+        for ksplit in ((1, 2, 4) if kg == 1 else (1, 2)):
+            zqfp.probe_force_tile_plan(bm, bn, ksplit, kg)
+            for rep in range(2):  # a fragment register read before its data arrived would differ from run to run
+                Y, Y_o, Sabs = _gemm_case(M, K, N, G, mode, r)
+                check_gemm(Y, Y_o, Sabs, f"{bm}x{bn} tiles, {kg} wave group(s), {K // 128 // ksplit // kg} k-tile(s) per group")
+    finally:
+        zqfp.probe_force_tile_plan(0, 0, 0)

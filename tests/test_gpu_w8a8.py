@@ -103,6 +103,25 @@ def test_gemm_full_size_sampled(name, M):
         assert ratio <= WORST and fro <= 1e-4
 
 
+@pytest.mark.parametrize("bm,kg", [(64, 1), (64, 2), (128, 1)])
+def test_gemm_every_tile_shape_of_the_fp8_weight_form(bm, kg):
+    """The launcher picks 128 x 128 or 64 x 128 tiles (the latter with one or two wave groups) from the problem
+    size; here each is forced onto ragged problems: many k-steps, and fewer k-steps than LDS stages (run twice:
+    a fragment register used before its data arrived would differ from run to run)."""
+    try:
+        zqfp.probe_force_tile_plan(bm, 128, 1, kg)
+        for (M, K, N, G, mode, r), reps in (((300, 1536, 1000, 128, 2, 8), 1), ((200, 256, 264, 128, 1, 0), 2),
+                                            ((130, 128, 136, 128, 1, 3), 2)):
+            for accum in (zqfp.ACCUM_EXACT, zqfp.ACCUM_FAST):
+                for _ in range(reps):
+                    Y, Y_o, Sabs = _case(M, K, N, G, mode, r, accum=accum)
+                    err = np.abs(Y.astype(np.float64) - Y_o)
+                    assert np.all(err <= WORST * Sabs + 1e-300), f"{bm}x128 kg {kg} K {K} accum {accum}: {(err / np.maximum(Sabs, 1e-300)).max():.3e}"
+                    assert np.linalg.norm(Y - Y_o) / max(np.linalg.norm(Y_o), 1e-300) <= 1e-4
+    finally:
+        zqfp.probe_force_tile_plan(0, 0, 0)
+
+
 def test_bf16_output_and_argument_checks():
     Y, Y_o, Sabs = _case(100, 512, 200, 128, 2, 8, out_dtype=torch.bfloat16)
     want = torch.from_numpy(Y_o).to(torch.bfloat16).float().numpy().astype(np.float64)
