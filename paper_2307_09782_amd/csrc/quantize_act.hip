@@ -388,10 +388,13 @@ __global__ __launch_bounds__(NT) void k_quantize_act(const uint16_t* __restrict_
 // the reductions are wave shuffles only, and no barrier or LDS is involved; 16 waves per compute
 // unit keep 8 * MAXC KB of loads in flight each.
 // ---------------------------------------------------------------------------
-// LORC: the rank-8 left factor T = y . U rides along; the four waves of a workgroup walk U in step, so three
-// of them are served by the vector cache.
+// LORC: the rank-8 left factor T = y . U rides along.  The workgroup then has eight waves (eight tokens) and keeps
+// the whole of U (K x 8 binary16 values, 16 bytes per row, at most 128 KB) in LDS: the loads of U are issued ahead of
+// the row's own, so that they are the first to land, and the multiply-adds of a chunk start as soon as that chunk
+// of the row has arrived, while the rest of the row is still on its way -- there is no barrier and no further load
+// in the loop.
 template <int MAXC, int NORM, bool LORC>
-__global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
+__global__ __launch_bounds__(LORC ? 512 : 256) void k_quantize_rows(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
                                                      uint8_t* __restrict__ Xq, float* __restrict__ sx,
                                                      const uint16_t* __restrict__ U, float* __restrict__ T, Producer pr)
 {
@@ -399,8 +402,9 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
     const uint16_t* __restrict__ bias = pr.bias;
     const float eps = pr.eps;
     const int lane = threadIdx.x & 63;
-    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    bool live = true;  // LORC: the four waves stage U together, so a wave past the last token stays, repeats that token and stores nothing
+    constexpr int kRowsPerWg = LORC ? 8 : 4;
+    int64_t row = (int64_t)blockIdx.x * kRowsPerWg + (threadIdx.x >> 6);
+    bool live = true;  // LORC: the waves stage U together, so a wave past the last token stays, repeats that token and stores nothing
     if (row >= M) {
         if constexpr (!LORC) return;  // whole waves leave; nothing below synchronises across waves
         live = false;
@@ -410,12 +414,46 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
     uint2* qrow = reinterpret_cast<uint2*>(Xq + row * K);
     const int nchunk = (int)(K / 8);
 
+    // LORC: row k of U is 8 binary16 values, one uint4.  Thread t fetches row 512 c + t of every 512-row chunk c
+    // (past K: the last row; the row's elements are zero there) and stores it at slot (t % 8) * 64 + t / 8 of the
+    // chunk: lane l, which holds elements 8 l .. 8 l + 7 of the chunk, then finds the row of its i-th element at
+    // slot 64 i + l, consecutive across the wave (conflict-free 16-byte reads, and no exchange of elements).
+    // Every load of this form is unconditional (indices past the end are clamped into the row, what they fetch is
+    // replaced by zeros afterwards): with loads inside branches the compiler can no longer count the outstanding ones
+    // and waits for all of them at the first use of any.
+    extern __shared__ __attribute__((aligned(16))) uint4 s_u[];  // LORC: MAXC * 512 slots
+    uint4 ureg[LORC ? MAXC : 1];
+    if constexpr (LORC) {
+        const uint4* u4 = reinterpret_cast<const uint4*>(U);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int64_t k = (int64_t)c * 512 + threadIdx.x;
+            ureg[c] = u4[k < K ? k : K - 1];
+        }
+    }
     uint4 v[MAXC];
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int idx = c * 64 + lane;
-        v[c] = make_uint4(0, 0, 0, 0);
-        if (idx < nchunk) v[c] = xrow[idx];
+        if constexpr (LORC) {
+            v[c] = xrow[idx < nchunk ? idx : nchunk - 1];
+        } else {
+            v[c] = make_uint4(0, 0, 0, 0);
+            if (idx < nchunk) v[c] = xrow[idx];
+        }
+    }
+    if constexpr (LORC) {  // needs the loads of U only: the row's are younger
+        const int slot = (threadIdx.x & 7) * 64 + (threadIdx.x >> 3);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) s_u[c * 512 + slot] = ureg[c];
+        __syncthreads();
+    }
+    auto zero_past_end = [&](int c) {  // LORC: what the clamped loads fetched past the row's end
+        if (c * 64 + lane >= nchunk) v[c] = make_uint4(0, 0, 0, 0);
+    };
+    if constexpr (LORC && NORM != 0) {
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) zero_past_end(c);
     }
     if constexpr (NORM != 0) {
         if (pr.other != nullptr || NORM == 4) {
@@ -467,37 +505,17 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
     }
     float acc[8];
     if constexpr (LORC) {
-        // A lane holds 8 consecutive elements; it trades them, through the wave's own 1 KB of LDS, for elements
-        // lane, lane + 64, ... of the chunk's 512, so that lane l meets rows l, l + 64, ... of U.  The 512 rows of U
-        // that a chunk needs (8 KB) are staged in LDS once per workgroup and serve its four tokens: every token
-        // re-reading U from L2 made the call twice as slow as the plain quantizer at 2048 tokens.  Two buffers, so one
-        // barrier per chunk: chunk c + 1 is fetched into the other buffer while chunk c is multiplied.
-        __shared__ __attribute__((aligned(16))) uint16_t s_x[4][512];
-        __shared__ __attribute__((aligned(16))) uint4 s_u[2][512];
-        const int wave = threadIdx.x >> 6;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-        const uint4* u4 = reinterpret_cast<const uint4*>(U);  // row k of U (8 binary16 values) is u4[k]
-        auto fetch_u = [&](int c, uint4& a, uint4& b) {  // rows wave * 128 + lane and + 64 of chunk c (past K: the last row; x is zero there)
-            const int64_t k0 = (int64_t)c * 512 + wave * 128 + lane;
-            a = u4[k0 < K ? k0 : K - 1];
-            b = u4[k0 + 64 < K ? k0 + 64 : K - 1];
-        };
-        uint4 ua, ub;
-        fetch_u(0, ua, ub);
-        s_u[0][wave * 128 + lane] = ua;
-        s_u[0][wave * 128 + 64 + lane] = ub;
-        __syncthreads();
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
-            if (c * 64 < nchunk) {  // the same for the whole workgroup
-                const bool more = (c + 1) * 64 < nchunk;
-                if (more) fetch_u(c + 1, ua, ub);
-                *reinterpret_cast<uint4*>(&s_x[wave][lane * 8]) = v[c];  // same wave writes and reads: no barrier
+            if constexpr (NORM == 0) zero_past_end(c);  // here, so that chunk c waits for its own load only
+            if (c * 64 < nchunk) {  // the same for the whole workgroup; lanes past the row's end hold zeros
+                const uint32_t xw[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float x = __uint_as_float((uint32_t)s_x[wave][lane + 64 * i] << 16);
-                    const uint4 u = s_u[c & 1][64 * i + lane];
+                    const float x = __uint_as_float((i & 1) ? (xw[i >> 1] & 0xffff0000u) : (xw[i >> 1] << 16));
+                    const uint4 u = s_u[c * 512 + 64 * i + lane];
                     const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -508,11 +526,6 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
                         acc[2 * q + 1] = fmaf(x, (float)p[1], acc[2 * q + 1]);
                     }
                 }
-                if (more) {  // the other buffer's readers (chunk c - 1) passed the previous barrier
-                    s_u[(c + 1) & 1][wave * 128 + lane] = ua;
-                    s_u[(c + 1) & 1][wave * 128 + 64 + lane] = ub;
-                }
-                __syncthreads();
             }
         }
     }
@@ -544,6 +557,22 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const uint16_t* __restric
     }
 }
 
+// the wave-per-token kernel with the rank-8 factor: eight tokens per workgroup, all of U in dynamic LDS
+template <int MAXC, int KIND>
+hipError_t launch_rows_lorc(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const uint16_t* U,
+                            float* T, const Producer& pr, hipStream_t s)
+{
+    auto kern = k_quantize_rows<MAXC, KIND, true>;
+    const size_t smem = (size_t)MAXC * 512 * sizeof(uint4);
+    static OnceStatus attr;  // raising the dynamic LDS limit is a per-function, per-process setting
+    if (hipError_t e = run_once(attr, [&] {
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        }); e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((M + 7) / 8)), dim3(512), smem, s, X, M, K, ldx, Xq, sx, U, T, pr);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx,
@@ -551,15 +580,20 @@ hipError_t launch_quantize_act(const uint16_t* X, int64_t M, int64_t K, int64_t 
 {
     if (M == 0) return hipSuccess;
     const int kind = pr.kind;
-    // many tokens: one wave per token, without the LoRC factor or with the rank-8 one (its four waves share U through
-    // LDS; 4096 x 4096 with the factor: 25.3 -> 21.5 us against the workgroup-per-token kernel, 4096 x 2048: 19.1 -> 12.9).
-    // With the factor the call is bound by issuing the K x 8 multiply-adds per token, not by memory.
+    // many tokens: one wave per token, without the LoRC factor or with the rank-8 one (U in LDS)
     if (M >= 1024 && K <= 8192 && (r == 0 || r == 8)) {
         const dim3 g4((unsigned)((M + 3) / 4));
 #define ZQ_ROWS_N(MAXC, KIND)                                                                                               \
     do {                                                                                                                    \
-        if (r == 8) hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND, true>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, U, T, pr);  \
-        else hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND, false>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, U, T, pr);        \
+        if (r == 8) {  /* every chunk's load of U and of the row is issued: a tight chunk count wastes none */                 \
+            constexpr int C1 = MAXC == 16 ? 10 : MAXC == 8 ? 6 : MAXC, C2 = MAXC == 16 ? 12 : MAXC;                              \
+            hipError_t e = K <= 512 * C1   ? launch_rows_lorc<C1, KIND>(X, M, K, ldx, Xq, sx, U, T, pr, s)                       \
+                           : K <= 512 * C2 ? launch_rows_lorc<C2, KIND>(X, M, K, ldx, Xq, sx, U, T, pr, s)                       \
+                                           : launch_rows_lorc<MAXC, KIND>(X, M, K, ldx, Xq, sx, U, T, pr, s);                   \
+            if (e != hipSuccess) return e;                                                                                      \
+        } else {                                                                                                                \
+            hipLaunchKernelGGL((k_quantize_rows<MAXC, KIND, false>), g4, dim3(256), 0, s, X, M, K, ldx, Xq, sx, U, T, pr);        \
+        }                                                                                                                       \
     } while (0)
 #define ZQ_ROWS(MAXC)                          \
     do {                                       \

@@ -89,6 +89,22 @@ def test_lorc_left_factor(name, M, r):
     assert (err / Tabs).max() <= 2.0 ** -18
 
 
+@pytest.mark.parametrize("K,M", [(2688, 1029), (640, 1024), (5632, 1031), (6400, 1025)])
+def test_lorc_left_factor_many_tokens_rows_that_end_inside_a_chunk(K, M):
+    """The wave-per-token kernel walks a row in chunks of 512 elements and stages all of U in LDS in the same chunks: here the
+    row ends inside a chunk (K is a multiple of 128, not of 512), the token count leaves the last workgroup partly
+    empty, and K picks each of the chunk counts the launcher has."""
+    cfg = inputs.Config("q", K, 256, (M,), 128, 1, 0.01, 0, 20.0, 8, 11)
+    X = inputs.make_x(cfg, M)
+    U, _ = inputs.make_uv(cfg, rank=8)
+    T_o, Tabs = oracle.lorc_left(X, U)
+    Xq_o, sx_o = oracle.quantize_act(X)
+    Xq, sx, T = zqfp.quantize_act_fp8(bf16_tensor(X), f16_tensor(U))
+    assert np.array_equal(_sync_np(Xq), Xq_o) and bits_equal_f32(_sync_np(sx), sx_o)
+    err = np.abs(_sync_np(T).astype(np.float64) - T_o)
+    assert (err / Tabs).max() <= 2.0 ** -18
+
+
 # ------------------------------------------------------------------ packer
 def _pack_and_compare(W, G, mode, cols=None):
     K, N = W.shape
