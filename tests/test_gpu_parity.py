@@ -779,3 +779,33 @@ def test_gemm_every_tile_shape_on_pipelines_shorter_than_the_stages(bm, bn, kg):
                 check_gemm(Y, Y_o, Sabs, f"{bm}x{bn} tiles, {kg} wave group(s), {K // 128 // ksplit // kg} k-tile(s) per group")
     finally:
         zqfp.probe_force_tile_plan(0, 0, 0)
+
+
+def test_gemm_repeated_launches_give_the_same_bits_on_every_tile_shape():
+    """A register or an LDS stage read before its data has arrived shows as results that differ from launch to
+    launch; so every tile shape (FP4 and FP8 weights, both accumulation modes, unsplit and with K in slices) is
+    launched several times on ragged problems with long and with very short pipelines and the outputs are
+    compared bit for bit.  (What the bits should be is the other tests' business.)"""
+    shapes4 = [(64, 128, 1), (64, 128, 2), (64, 192, 1), (64, 192, 2), (64, 256, 1), (64, 256, 2),
+               (128, 128, 1), (128, 192, 1), (128, 256, 1), (256, 256, 1)]
+    shapes8 = [(64, 128, 1), (64, 128, 2), (128, 128, 1)]
+    try:
+        for M, K, N in ((300, 1536, 1000), (531, 256, 520), (77, 128, 200), (260, 2304, 264)):
+            cfg = inputs.Config("d", K, N, (M,), 128, 1, 0.01, 0, 20.0, 0, 5)
+            W = bf16_tensor(inputs.make_w(cfg))
+            Xq, sx = zqfp.quantize_act_fp8(bf16_tensor(inputs.make_x(cfg, M)))
+            p4, p8 = zqfp.pack_weight_fp4(W, 128, 1), zqfp.pack_weight_fp8(W, 128, 1)
+            for wb, shapes in ((4, shapes4), (8, shapes8)):
+                for bm, bn, kg in shapes:
+                    for ksplit in ((1, 2, 3) if wb == 4 else (1,)):
+                        if K // 128 < ksplit * kg:
+                            continue
+                        for accum in (zqfp.ACCUM_EXACT, zqfp.ACCUM_FAST):
+                            zqfp.probe_force_tile_plan(bm, bn, ksplit, kg)
+                            outs = [zqfp.w4a8_gemm(Xq, sx, p4, N, 128, accum=accum) if wb == 4
+                                    else zqfp.w8a8_gemm(Xq, sx, p8, N, 128, accum=accum) for _ in range(5)]
+                            torch.cuda.synchronize()
+                            assert all(torch.equal(outs[0], o) for o in outs[1:]), \
+                                f"wb {wb} M {M} K {K} N {N}: {bm}x{bn} tiles, {kg} group(s), K in {ksplit}, accum {accum}"
+    finally:
+        zqfp.probe_force_tile_plan(0, 0, 0)
