@@ -415,9 +415,12 @@ __global__ __launch_bounds__(LORC ? 512 : 256) void k_quantize_rows(const uint16
     const int nchunk = (int)(K / 8);
 
     // LORC: row k of U is 8 binary16 values, one uint4.  Thread t fetches row 512 c + t of every 512-row chunk c
-    // (past K: the last row; the row's elements are zero there) and stores it at slot (t % 8) * 64 + t / 8 of the
-    // chunk: lane l, which holds elements 8 l .. 8 l + 7 of the chunk, then finds the row of its i-th element at
-    // slot 64 i + l, consecutive across the wave (conflict-free 16-byte reads, and no exchange of elements).
+    // (past K: the last row; the row's elements are zero there) and stores it at slot 64 i + (l ^ 2 i) of the
+    // chunk, i = t % 8, l = t / 8: lane l, which holds elements 8 l .. 8 l + 7 of the chunk, then finds the row of
+    // its i-th element at slot 64 i + (l ^ 2 i) -- for a fixed i the 64 lanes read 64 consecutive slots in a
+    // permuted order (conflict-free 16-byte reads, no exchange of elements), and the sixteen lanes that store
+    // together (two values of l, all eight i) hit sixteen different slots of a 16-slot block (without the XOR
+    // they would hit two, eight lanes each).
     // Every load of this form is unconditional (indices past the end are clamped into the row, what they fetch is
     // replaced by zeros afterwards): with loads inside branches the compiler can no longer count the outstanding ones
     // and waits for all of them at the first use of any.
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(LORC ? 512 : 256) void k_quantize_rows(const uint16
         }
     }
     if constexpr (LORC) {  // needs the loads of U only: the row's are younger
-        const int slot = (threadIdx.x & 7) * 64 + (threadIdx.x >> 3);
+        const int slot = (threadIdx.x & 7) * 64 + ((threadIdx.x >> 3) ^ (2 * (threadIdx.x & 7)));
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) s_u[c * 512 + slot] = ureg[c];
         __syncthreads();
@@ -515,7 +518,7 @@ __global__ __launch_bounds__(LORC ? 512 : 256) void k_quantize_rows(const uint16
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float x = __uint_as_float((i & 1) ? (xw[i >> 1] & 0xffff0000u) : (xw[i >> 1] << 16));
-                    const uint4 u = s_u[c * 512 + 64 * i + lane];
+                    const uint4 u = s_u[c * 512 + 64 * i + (lane ^ (2 * i))];
                     const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
