@@ -71,7 +71,7 @@ def _case(M, K, N, G, mode, r, seed_cfg="tiny", accum=zqfp.ACCUM_EXACT, samples=
 
 SMALL = [
     (16, 256, 256, 128, 1, 0), (1, 256, 48, 128, 2, 0), (5, 384, 200, 384, 1, 3), (33, 512, 37, 256, 2, 0),
-    (64, 1024, 272, 128, 1, 8), (48, 128, 64, 128, 1, 2),                      # streaming form, up to 64 tokens
+    (64, 1024, 272, 128, 1, 8), (48, 128, 64, 128, 1, 2), (20, 640, 300, 128, 2, 8),  # streaming form (few tokens, narrow N, small matrices) and small tiles
     (65, 256, 130, 128, 2, 0), (77, 512, 200, 128, 2, 8), (200, 1280, 400, 256, 2, 0), (129, 384, 130, 128, 1, 16),
     (300, 1536, 1000, 128, 1, 8), (128, 128, 128, 128, 1, 0),                  # tiled form: ragged M, N, one k-step, LoRC
 ]
