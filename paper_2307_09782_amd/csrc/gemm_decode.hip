@@ -38,7 +38,9 @@ struct FusedIn {
     float* sx_out;      // [M], or null
 };
 
-template <int NW, int KPW, int NB, bool EXACT, bool LR, bool FUSED = false>
+// WB: weight bits.  8 = E4M3 weights (the W8A8 rows of the paper's Table 2 with FP8 on both sides): a strip's
+// k-tile is then two 1 KB halves, the first and second four registers of the B operand.
+template <int NW, int KPW, int NB, bool EXACT, bool LR, bool FUSED = false, int WB = 4>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void k_gemm_decode(
     const uint8_t* __restrict__ Xq, const float* __restrict__ sx, int M, const uint8_t* __restrict__ blob, BlobLayout L,
     Lorc lorc, void* __restrict__ Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len, float* __restrict__ partial,
@@ -109,6 +111,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const float* colscale = reinterpret_cast<const float*>(blob + L.off_colscale);
 
     u32x4 b[NB][KPW];
+    u32x4 bh[WB == 8 ? NB : 1][KPW];  // E4M3 weights: the fragments' second halves
     uint32_t e[NB][KPW];
 
     // ---- epilogue operands.  Thread t (mod 256) owns output (row t / 16, column t % 16) of every
@@ -140,7 +143,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
             const int kt = min(wave + kWaves * u, nkt - 1);  // clamped duplicates are multiplied by zero fragments
-            b[buf][u] = reinterpret_cast<const u32x4*>(codes + ((strip * nkt_all + kt0 + kt) << 10))[lane];
+            if constexpr (WB == 8) {
+                const u32x4* f = reinterpret_cast<const u32x4*>(codes + ((strip * nkt_all + kt0 + kt) << 11));
+                b[buf][u] = f[lane];
+                bh[buf][u] = f[64 + lane];
+            } else {
+                b[buf][u] = reinterpret_cast<const u32x4*>(codes + ((strip * nkt_all + kt0 + kt) << 10))[lane];
+            }
             e[buf][u] = (exq + strip * L.ngq * 16)[(stored_group(u) >> 2) * 16 + col];
         }
         const int64_t n = min(strip * 16 + ec, L.N - 1);
@@ -156,10 +165,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
-            const v8i bv = {(int)b[buf][u][0], (int)b[buf][u][1], (int)b[buf][u][2], (int)b[buf][u][3], 0, 0, 0, 0};
+            v8i bv = {(int)b[buf][u][0], (int)b[buf][u][1], (int)b[buf][u][2], (int)b[buf][u][3], 0, 0, 0, 0};
+            if constexpr (WB == 8) {
+                bv[4] = (int)bh[buf][u][0]; bv[5] = (int)bh[buf][u][1]; bv[6] = (int)bh[buf][u][2]; bv[7] = (int)bh[buf][u][3];
+            }
+            constexpr int BLGP = WB == 8 ? 0 : 4;  // B is E4M3 or E2M1
             const int sc = (int)(e[buf][u] >> (8 * (stored_group(u) & 3)));
             v4f& acc = (u & 1) ? acc1 : acc0;
-            // cbsz 0: A is E4M3; blgp 4: B is E2M1; A scale byte 127 = 2^0; B scale = group exponent
+            // cbsz 0: A is E4M3; A scale byte 127 = 2^0; B scale = group exponent
             if constexpr (EXACT) {
                 v4f& accl = (u & 1) ? acc3 : acc2;
                 v8i hi;
@@ -170,10 +183,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
                 } else {
                     hi = ahi[u];
                 }
-                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc, 0, 4, 0, 127, 0, sc);
-                accl = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, accl, 0, 4, 0, 127, 0, sc);
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(hi, bv, acc, 0, BLGP, 0, 127, 0, sc);
+                accl = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, accl, 0, BLGP, 0, 127, 0, sc);
             } else {
-                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, acc, 0, 4, 0, 127, 0, sc);
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(afr[u], bv, acc, 0, BLGP, 0, 127, 0, sc);
             }
         }
         *reinterpret_cast<v4f*>(&s_red[par][wave][lane][0]) = EXACT ? (acc0 + acc1) + (acc2 + acc3) : acc0 + acc1;
@@ -283,7 +296,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     }
 }
 
-template <int NW, int KPW, int NB>
+template <int NW, int KPW, int NB, int WB = 4>
 hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float* sx, int M, const uint8_t* blob,
                 const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype, int nchunks, int chunk_len,
                 float* partial, const FusedIn& fin, hipStream_t s)
@@ -296,18 +309,18 @@ hipError_t launch_kpw(unsigned grid, bool exact, const uint8_t* Xq, const float*
     if (smem > 0) {
         static OnceStatus raised;
         if (hipError_t e = run_once(raised, [&] {
-                hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, false>),
+                hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, false, false, WB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
                 if (e1 != hipSuccess) return e1;
-                return hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, true>),
+                return hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_decode<NW, KPW, NB, true, true, false, WB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             }); e != hipSuccess)
             return e;
     }
 #define ZQ_LAUNCH(EX, LR, FU) \
-    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR, FU>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial, fin)
+    hipLaunchKernelGGL((k_gemm_decode<NW, KPW, NB, EX, LR, FU, WB>), dim3(grid), dim3(64 * NW), smem, s, Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, nchunks, chunk_len, partial, fin)
     if (fin.X != nullptr) {
-        if constexpr (KPW <= 4) {
+        if constexpr (KPW <= 4 && WB == 4) {
             if (exact) ZQ_LAUNCH(true, false, true); else ZQ_LAUNCH(false, false, true);
         } else {
             return hipErrorInvalidValue;  // not reached: the caller checks gemm_decode_fused_supported
@@ -346,6 +359,29 @@ bool gemm_decode_supported(int64_t M, const BlobLayout& L, const void* workspace
     // longer K: in chunks through the workspace, if there are strips enough to give every workgroup
     // several (below that the streaming kernel, one launch and no prologue per chunk, is faster)
     return workspace != nullptr && L.nstrips * plan_decode(L.nkt).chunks >= 1024;
+}
+
+// E4M3 weights, at most 16 tokens and 40 k-tiles: a fragment is twice the registers of an FP4 one, so a wave holds at
+// most five k-tiles (with two fragment buffers) before it spills, and there are no chunks (the W8A8 entry point takes
+// no workspace).  Longer K stays with the streaming kernel.
+bool gemm_w8_decode_supported(int64_t M, const BlobLayout& L) { return M >= 1 && M <= 16 && L.nkt <= 40 && L.N >= 16; }
+
+hipError_t launch_gemm_w8_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob, const BlobLayout& L,
+                                 Lorc lorc, void* Y, int64_t ldy, int out_dtype, int accum, hipStream_t s)
+{
+    const FusedIn fin{nullptr, 0, nullptr, nullptr};
+    if (L.N == 0) return hipSuccess;
+    const int cus = compute_units();
+    const bool exact = accum == 0;
+    const int m = (int)M, len = (int)L.nkt;
+    const unsigned grid = (unsigned)(L.nstrips < cus ? L.nstrips : cus);
+#define ZQ_W8(KPW, NB) launch_kpw<8, KPW, NB, 8>(grid, exact, Xq, sx, m, blob, L, lorc, Y, ldy, out_dtype, 1, len, nullptr, fin, s)
+    if (len <= 8) return ZQ_W8(1, 4);
+    if (len <= 16) return ZQ_W8(2, 4);
+    if (len <= 24) return ZQ_W8(3, 3);
+    if (len <= 32) return ZQ_W8(4, 2);
+    return ZQ_W8(5, 2);
+#undef ZQ_W8
 }
 
 bool gemm_decode_fused_supported(int64_t M, const BlobLayout& L, int r)

@@ -250,7 +250,9 @@ int zqfp_w8a8_gemm(const uint8_t* Xq, const float* sx, int64_t M, int64_t K, con
     // the streaming kernel: at most 16 tokens, fewer than 64 output channels, or up to 32 tokens on a small matrix (measured: 7B QKV
     // at 17 tokens 17.6 us against the tiled kernel's 20.3; on the 70B FFN matrix the tiled kernel wins from 17 tokens on, 39 us against 64)
     const bool small = M <= 32 && K * N <= (int64_t)1 << 26;
-    hipError_t e = !zqfp::gemm_tile_supported(M, L) || small
+    hipError_t e = zqfp::gemm_w8_decode_supported(M, L)
+                       ? zqfp::launch_gemm_w8_decode(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
+                   : !zqfp::gemm_tile_supported(M, L) || small
                        ? zqfp::launch_gemm_stream(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s)
                        : zqfp::launch_gemm_w8_tile(Xq, sx, M, blob, L, lorc, Y, ldy, out_dtype, accum, s);
     return e == hipSuccess ? ZQFP_OK : hip_fail(e);

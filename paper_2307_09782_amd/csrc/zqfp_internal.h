@@ -294,6 +294,11 @@ hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* code
 hipError_t launch_gemm_stream(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
                               const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
                               int accum, hipStream_t s);
+// W8A8 (E4M3 weights, L.wbits == 8), at most 16 tokens: the persistent weight-streaming kernel
+bool gemm_w8_decode_supported(int64_t M, const BlobLayout& L);
+hipError_t launch_gemm_w8_decode(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
+                                 const BlobLayout& L, Lorc lorc, void* Y, int64_t ldy, int out_dtype,
+                                 int accum, hipStream_t s);
 // W8A8 (E4M3 weights, L.wbits == 8), more than 16 tokens: the tiled kernel with two-register-quad B operands,
 // 128 x 128 or 64 x 128 tiles
 hipError_t launch_gemm_w8_tile(const uint8_t* Xq, const float* sx, int64_t M, const uint8_t* blob,
