@@ -738,16 +738,17 @@ struct TileKind {
     float e, s;
 };
 constexpr TileKind kTileKinds[] = {
-    {64, 128, 2, 3.3f, 0.406f},   // two wave groups: one workgroup per compute unit, so at most 256 tiles
-    {64, 192, 2, 4.3f, 0.570f},
-    {64, 256, 2, 5.3f, 0.666f},
-    {64, 128, 1, 3.5f, 0.325f},
-    {64, 192, 1, 4.5f, 0.434f},
-    {64, 256, 1, 5.5f, 0.530f},
-    {128, 128, 1, 5.5f, 0.594f},
-    {128, 192, 1, 7.5f, 0.780f},
-    {128, 256, 1, 9.5f, 0.990f},
-    {256, 256, 1, 17.5f, 2.000f},
+    // least-squares fit (relative error) to 527 timings: seven weight shapes with 16 ... 224 k-tiles, 64 ... 4096 tokens
+    {64, 128, 2, 3.8f, 0.368f},   // two wave groups: one workgroup per compute unit, so at most 256 tiles
+    {64, 192, 2, 6.0f, 0.477f},
+    {64, 256, 2, 6.8f, 0.584f},
+    {64, 128, 1, 2.1f, 0.368f},
+    {64, 192, 1, 3.3f, 0.464f},
+    {64, 256, 1, 4.5f, 0.549f},
+    {128, 128, 1, 4.3f, 0.632f},
+    {128, 192, 1, 6.6f, 0.778f},
+    {128, 256, 1, 8.6f, 0.928f},
+    {256, 256, 1, 12.4f, 2.009f},
 };
 
 TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
@@ -763,9 +764,21 @@ TilePlan plan_tiles(int64_t M, int64_t Np, int64_t nkt)
         if (want > 16) want = 16;
         if (want > nkt / 8) want = nkt / 8;
         if (want >= 3) {
-            p.kslice = (int)((nkt + want - 1) / want);
-            p.ksplit = (int)((nkt + p.kslice - 1) / p.kslice);
-            return p;
+            // The slices' trip through memory must pay for itself: against the un-split launch (two wave groups, at
+            // most one tile per compute unit here) the split saves K-steps and costs a second kernel and the
+            // partial sums written, read back and summed.  The launch will halve the slice count where two wave
+            // groups can take the halves (launch_pick), which is what is priced.  Measured on K = N = 4096: splitting
+            // wins up to 128 tokens (17.0 against 18.1 us) and loses from 192 on (21.1 against 18.4 at 256), while
+            // K = 11008 gains at every token count that gets here (256 tokens: 29.6 against 38.1 us).
+            const int kslice = (int)((nkt + want - 1) / want), ksplit = (int)((nkt + kslice - 1) / kslice);
+            const float eff = (float)((ksplit + 1) / 2);
+            const float trip_us = (2.0f * eff + 1.0f) * (float)M * (float)Np * 4.0f / 2.5e6f;  // measured: 2.5 TB/s, second launch included
+            const float split_us = 3.8f + 0.368f * (float)nkt / eff + trip_us, unsplit_us = 3.8f + 0.368f * (float)nkt;
+            if (split_us < unsplit_us) {
+                p.kslice = kslice;
+                p.ksplit = ksplit;
+                return p;
+            }
         }
     }
     // Many rounds of large tiles: 128 x 256, two workgroups per compute unit that fill each other's gaps.
