@@ -560,14 +560,153 @@ __global__ __launch_bounds__(LORC ? 512 : 256) void k_quantize_rows(const uint16
     }
 }
 
+// The same with a helper wave per token (plain and ReLU forms, rows of at most 5120 elements): 2048 tokens are only
+// eight waves per compute unit, and a lone chain of K x 8 multiply-adds per token is what the call then waits for
+// (one or two waves per SIMD issue a vector instruction every 12 or 6 cycles).  Sixteen waves per workgroup: wave
+// w < 8 owns token w as before but multiplies only the first H chunks of its row; wave w + 8 fetches the other
+// chunks of the same row (the requests of the token wave for them, issued behind the staging barrier, then hit in
+// L2), multiplies them and hands its eight partial sums over through LDS.  Both kinds issue the same number of
+// loads ahead of the barrier, in the same straight-line code, so the compiler's load counts stay exact.
+template <int MAXC, int NORM>
+__global__ __launch_bounds__(1024) void k_quantize_rows_helped(const uint16_t* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
+                                                             uint8_t* __restrict__ Xq, float* __restrict__ sx,
+                                                             const uint16_t* __restrict__ U, float* __restrict__ T)
+{
+    static_assert(NORM == 0 || NORM == 3, "element-wise producers only: a helper has half a row");
+    constexpr int H = (MAXC + 1) / 2, R = MAXC - H;  // chunks multiplied by the token wave / by its helper
+    extern __shared__ __attribute__((aligned(16))) uint4 s_u[];  // MAXC * 512 slots, as in k_quantize_rows
+    __shared__ float s_part[8][8];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const bool helper = w >= 8;  // wave-uniform
+    int64_t row = (int64_t)blockIdx.x * 8 + (w & 7);
+    const bool live = row < M;
+    if (!live) row = M - 1;  // stays for the barriers, repeats the last token, stores nothing
+    const uint4* xrow = reinterpret_cast<const uint4*>(X + row * ldx);
+    uint2* qrow = reinterpret_cast<uint2*>(Xq + row * K);
+    const int nchunk = (int)(K / 8);
+    const int base = helper ? H : 0;  // first chunk of this wave's share
+
+    // U: the 512 threads of each half of the workgroup take the chunks of one parity (a chunk past the last is the
+    // last again: the same rows to the same slots)
+    uint4 ureg[H];
+    const int st = threadIdx.x & 511, par = threadIdx.x >> 9;
+    const uint4* u4 = reinterpret_cast<const uint4*>(U);
+#pragma unroll
+    for (int j = 0; j < H; ++j) {
+        const int c = min(2 * j + par, MAXC - 1);
+        const int64_t k = (int64_t)c * 512 + st;
+        ureg[j] = u4[k < K ? k : K - 1];
+    }
+    uint4 f[H];  // this wave's share of the row (a helper with one chunk less fetches its last one twice)
+#pragma unroll
+    for (int c = 0; c < H; ++c) {
+        const int idx = min(base + c, MAXC - 1) * 64 + lane;
+        f[c] = xrow[idx < nchunk ? idx : nchunk - 1];
+    }
+    {
+        const int slot = (st & 7) * 64 + ((st >> 3) ^ (2 * (st & 7)));
+#pragma unroll
+        for (int j = 0; j < H; ++j) s_u[min(2 * j + par, MAXC - 1) * 512 + slot] = ureg[j];
+    }
+    __syncthreads();
+    // the rest of the row, which the token wave needs for the maximum and the codes (its helper asked for the same
+    // lines ahead of the barrier).  Issued by both kinds of wave, so that no load sits in a branch.
+    uint4 g[R > 0 ? R : 1];
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+        const int idx = (H + c) * 64 + lane;
+        g[c] = xrow[idx < nchunk ? idx : nchunk - 1];
+    }
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < H; ++c) {
+        const int ch = base + c;  // the chunk in f[c]; a helper's repeated last chunk counts for nothing
+        if (ch * 64 + lane >= nchunk || ch >= MAXC) f[c] = make_uint4(0, 0, 0, 0);
+        if constexpr (NORM == 3) f[c] = relu8(f[c]);
+        if (ch * 64 < nchunk && ch < MAXC) {  // wave-uniform
+            const uint32_t xw[4] = {f[c].x, f[c].y, f[c].z, f[c].w};
+            const uint4* su = s_u + ch * 512;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float x = __uint_as_float((i & 1) ? (xw[i >> 1] & 0xffff0000u) : (xw[i >> 1] << 16));
+                const uint4 u = su[64 * i + (lane ^ (2 * i))];
+                const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const half2_t p = __builtin_bit_cast(half2_t, uw[q]);  // widened inside the multiply-add, as above
+                    acc[2 * q] = fmaf(x, (float)p[0], acc[2 * q]);
+                    acc[2 * q + 1] = fmaf(x, (float)p[1], acc[2 * q + 1]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc[j] += __shfl_xor(acc[j], off);
+    }
+    float mine = acc[0];  // every lane holds all eight sums: lane j keeps the j-th
+#pragma unroll
+    for (int j = 1; j < 8; ++j) mine = lane == j ? acc[j] : mine;
+    if (helper) {
+        if (lane < 8) s_part[w - 8][lane] = mine;
+        __syncthreads();
+        return;
+    }
+    uint32_t am = 0;
+#pragma unroll
+    for (int c = 0; c < H; ++c) am = absmax_bits(am, f[c]);
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+        if ((H + c) * 64 + lane >= nchunk) g[c] = make_uint4(0, 0, 0, 0);
+        if constexpr (NORM == 3) g[c] = relu8(g[c]);
+        am = absmax_bits(am, g[c]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) am = max(am, (uint32_t)__shfl_xor((int)am, off));
+    float scale, inv;
+    token_scale(am, scale, inv);
+    if (lane == 0 && live) sx[row] = scale;
+#pragma unroll
+    for (int c = 0; c < H; ++c) {
+        const int idx = c * 64 + lane;
+        if (idx < nchunk && live) qrow[idx] = encode8(f[c], inv);
+    }
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+        const int idx = (H + c) * 64 + lane;
+        if (idx < nchunk && live) qrow[idx] = encode8(g[c], inv);
+    }
+    __syncthreads();  // the helper's sums are in LDS
+    if (lane < 8 && live) T[row * 8 + lane] = mine + s_part[w][lane];  // first half of the row plus second half: a fixed order
+}
+
 // the wave-per-token kernel with the rank-8 factor: eight tokens per workgroup, all of U in dynamic LDS
 template <int MAXC, int KIND>
 hipError_t launch_rows_lorc(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, float* sx, const uint16_t* U,
                             float* T, const Producer& pr, hipStream_t s)
 {
-    auto kern = k_quantize_rows<MAXC, KIND, true>;
     const size_t smem = (size_t)MAXC * 512 * sizeof(uint4);
     static OnceStatus attr;  // raising the dynamic LDS limit is a per-function, per-process setting
+    // A helper wave per token while every compute unit gets at most one workgroup (its 16 waves leave 128 registers
+    // each, hence rows of at most 5120 elements): 2048 x 5120 12.1 -> 11.0 us, 1024 x 5120 11.1 -> 9.9.  With more
+    // tokens the waves of later workgroups fill the SIMDs anyway and the helpers' second fetch of half of every row
+    // only costs (4096 x 4096: 16.6 -> 19.3 us), so the plain form stays.
+    if constexpr ((KIND == 0 || KIND == 3) && MAXC <= 10) {
+        if ((M + 7) / 8 <= compute_units()) {
+            auto kern = k_quantize_rows_helped<MAXC, KIND>;
+            static OnceStatus attr_helped;
+            if (hipError_t e = run_once(attr_helped, [&] {
+                    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+                }); e != hipSuccess)
+                return e;
+            hipLaunchKernelGGL(kern, dim3((unsigned)((M + 7) / 8)), dim3(1024), smem, s, X, M, K, ldx, Xq, sx, U, T);
+            return hipGetLastError();
+        }
+    }
+    auto kern = k_quantize_rows<MAXC, KIND, true>;
     if (hipError_t e = run_once(attr, [&] {
             return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         }); e != hipSuccess)

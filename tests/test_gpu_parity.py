@@ -89,11 +89,12 @@ def test_lorc_left_factor(name, M, r):
     assert (err / Tabs).max() <= 2.0 ** -18
 
 
-@pytest.mark.parametrize("K,M", [(2688, 1029), (640, 1024), (5632, 1031), (6400, 1025)])
+@pytest.mark.parametrize("K,M", [(2688, 1029), (640, 1024), (5632, 1031), (6400, 1025), (640, 2100), (2688, 2056)])
 def test_lorc_left_factor_many_tokens_rows_that_end_inside_a_chunk(K, M):
     """The wave-per-token kernel walks a row in chunks of 512 elements and stages all of U in LDS in the same chunks: here the
     row ends inside a chunk (K is a multiple of 128, not of 512), the token count leaves the last workgroup partly
-    empty, and K picks each of the chunk counts the launcher has."""
+    empty, and K picks each of the chunk counts the launcher has.  Up to 2048 tokens and 5120 elements a helper wave per
+    token multiplies the second half of the row; the last two cases have more tokens than that form takes."""
     cfg = inputs.Config("q", K, 256, (M,), 128, 1, 0.01, 0, 20.0, 8, 11)
     X = inputs.make_x(cfg, M)
     U, _ = inputs.make_uv(cfg, rank=8)
